@@ -1,0 +1,198 @@
+/*
+ * hcache.h -- C ABI of the MI355X-native HCache restoration library (libhcache.so).
+ *
+ * What the library does (paper Section 3.1): a serving system saves, per transformer
+ * layer, the hidden state that enters the layer for every token of a context.  To
+ * restore that context's KV cache it fetches the saved states of layer L from host
+ * storage and re-projects them: K = W_k * H, V = W_v * H.  The equations of the
+ * paper leave out the layer's input normalisation and the position embedding
+ * (Section 2.1); Section 5 names the device steps: a GEMM, then a kernel that
+ * applies RoPE to the re-projected keys and copies K/V into the (paged, Section 6
+ * "Baselines") KV cache.  Fetching layer L+1 overlaps the projection of layer L
+ * (Section 3.1, pipelined restoration; Section 5, "Pipelined state transmission").
+ * Host-side, the saved states live in fixed-size token chunks per layer (Section
+ * 4.2.1).
+ *
+ * Here every device step of one layer -- RMSNorm with the layer's gain, the fused
+ * K|V projection on bf16 matrix cores with fp32 accumulation, RoPE on K at each
+ * token's absolute position, one round-to-nearest-even conversion to bf16 and the
+ * scatter into block-table pages -- is ONE kernel launch.
+ *
+ * Conventions
+ *   - No exception crosses this boundary.  Every call returns an hc_status; on failure
+ *     hc_last_error() holds a message for the calling thread.
+ *   - "d_" arguments are DEVICE pointers (HBM) owned by the caller; "h_" arguments are
+ *     HOST pointers.  Device pointers must be 16-byte aligned (HC_EALIGN otherwise).
+ *   - `stream` arguments are hipStream_t values passed as void* (NULL = the null stream).
+ *     Launches are asynchronous on that stream; the library never synchronises a
+ *     caller's stream except where a function says so.
+ *   - All matrices are row-major; bf16 is the upper half of an IEEE binary32.
+ *   - A context (hc_ctx) belongs to the device that was current in hc_create and may be
+ *     used by one host thread at a time.
+ *   - Rows whose position cannot be mapped (outside the block table, unmapped block,
+ *     page outside the pool, position >= max_position) are SKIPPED, never written out of
+ *     bounds, and raise a sticky flag readable with hc_poll_device_error.
+ */
+#ifndef HCACHE_H
+#define HCACHE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t hc_status;
+enum {
+  HC_OK      = 0,
+  HC_EINVAL  = -1,  /* bad argument (null pointer, shape the kernels do not support)   */
+  HC_ERANGE  = -2,  /* index outside its table (layer, chunk, token range, capacity)   */
+  HC_EALIGN  = -3,  /* device pointer not 16-byte aligned                              */
+  HC_ENOMEM  = -4,  /* host or device allocation failed                                */
+  HC_EHIP    = -5,  /* a HIP runtime call failed; message carries hipGetErrorString    */
+  HC_ESTATE  = -6   /* call out of order (weights/pool not set, layer order in store)  */
+};
+
+/* bits of the sticky device error word */
+enum {
+  HC_DEV_BAD_POSITION = 1,  /* position < 0, >= max_position, or beyond the block table */
+  HC_DEV_BAD_PAGE     = 2   /* block table entry < 0 or >= num_pages                   */
+};
+
+typedef struct hc_ctx hc_ctx;
+typedef struct hc_store hc_store;
+
+/* Shape of the model whose KV cache is restored.  Supported by the kernels:
+ * d_model % 64 == 0, head_dim % 64 == 0, block_size a power of two, n_q_heads % n_kv_heads
+ * == 0.  rope_style 0 pairs feature i with i + head_dim/2, 1 pairs 2i with 2i+1 (the
+ * paper only cites RoFormer; both conventions are in use).  The RoPE table is built
+ * for positions [0, max_position). */
+typedef struct {
+  int32_t n_layers;
+  int32_t d_model;
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t head_dim;
+  int32_t block_size;
+  int32_t max_position;
+  int32_t rope_style;
+  float   rope_theta;
+  float   rms_eps;
+} hc_model_desc;
+
+/* Message describing the last failure on the calling thread ("" if none). */
+const char* hc_last_error(void);
+
+/* Library version string, e.g. "hcache-mi355x 0.1". */
+const char* hc_version(void);
+
+/* Validate `desc` only (no device work): HC_OK or HC_EINVAL with a message. */
+hc_status hc_validate_desc(const hc_model_desc* desc);
+
+/* Create a context on the current device.  Allocates the fp32 (cos, sin) RoPE table
+ * [max_position][head_dim/2] and fills it with an fp64-evaluated kernel; synchronises
+ * the null stream once.  *out is NULL on failure. */
+hc_status hc_create(const hc_model_desc* desc, hc_ctx** out);
+
+/* Free everything the context owns (packed weights, RoPE table, staging buffers).
+ * Synchronises the device first. */
+hc_status hc_destroy(hc_ctx* ctx);
+
+/* Give the context one layer's projection weights.
+ *   d_wkv   bf16 [2*d_kv, d_model]  nn.Linear layout; rows [0,d_kv) = W_k, [d_kv,2 d_kv) = W_v
+ *   d_gamma bf16 [d_model]          gain of the layer's input RMSNorm
+ * The library allocates its own device copy in the matrix-core friendly order it needs
+ * (gamma folded into the weights, one bf16 rounding) with a kernel on `stream`; the
+ * caller's buffers may be reused once `stream` has passed that point.  Calling it again
+ * for the same layer replaces the weights. */
+hc_status hc_set_layer_weights(hc_ctx* ctx, int32_t layer, const void* d_wkv,
+                               const void* d_gamma, void* stream);
+
+/* Register one layer's paged KV pool (borrowed, never freed by the library):
+ *   d_pool bf16 [num_pages][2 (0=K,1=V)][block_size][n_kv_heads][head_dim]            */
+hc_status hc_set_kv_pool(hc_ctx* ctx, int32_t layer, void* d_pool, int64_t num_pages);
+
+/* Restore layer `layer` of ONE context from hidden states already in HBM
+ * (Section 3.1 equations + Section 5 RoPE/copy step).
+ *   d_hidden      bf16  [n_tok, d_model]  saved inputs of the layer (before its RMSNorm)
+ *   d_positions   int32 [n_tok]           absolute positions; drive RoPE and the slot:
+ *                                         page = block_table[pos / block_size],
+ *                                         slot = pos % block_size
+ *   d_block_table int32 [n_blocks]        logical block -> page of the layer's pool
+ * n_tok == 0 is a no-op.  One asynchronous launch on `stream`. */
+hc_status hc_restore_kv(hc_ctx* ctx, int32_t layer, const void* d_hidden,
+                        const int32_t* d_positions, int32_t n_tok,
+                        const int32_t* d_block_table, int32_t n_blocks, void* stream);
+
+/* Ragged batch: the tokens of n_seq contexts concatenated into one projection.
+ *   d_cu_seqlens   int32 [n_seq + 1]          context s owns rows cu[s] .. cu[s+1]-1
+ *   d_block_tables int32 [n_seq][max_blocks]  one row per context, padded with -1
+ * h_total_tokens must equal cu[n_seq] (the host does not read device memory). */
+hc_status hc_restore_kv_ragged(hc_ctx* ctx, int32_t layer, const void* d_hidden,
+                               const int32_t* d_positions, int32_t h_total_tokens,
+                               const int32_t* d_cu_seqlens, int32_t n_seq,
+                               const int32_t* d_block_tables, int32_t max_blocks,
+                               void* stream);
+
+/* Read and clear the sticky device error word (HC_DEV_* bits).  Synchronises `stream`
+ * so that every launch queued on it has reported. */
+hc_status hc_poll_device_error(hc_ctx* ctx, void* stream, int32_t* out_flags);
+
+/* ---- host store of saved hidden states (Section 4.2.1, read side) -------------------
+ * A pinned host arena cut into chunks of `chunk_tokens` rows of d_model bf16; the
+ * states of (context, layer) are a list of chunks, the last one possibly part filled.
+ * Chunks are taken from the arena in the order the data arrives, i.e. in generation
+ * order (layer-before-token, Section 3.2 "C2"); restoration reads them one layer at a
+ * time through the index. */
+hc_status hc_store_create(int32_t n_layers, int32_t d_model, int32_t chunk_tokens,
+                          int64_t capacity_chunks, hc_store** out);
+/* Same, choosing the arena's memory: pinned != 0 -> hipHostMalloc (what asynchronous,
+ * full-rate host->HBM copies need; HC_ENOMEM if the runtime cannot provide it);
+ * pinned == 0 -> ordinary page-aligned host memory (hosts without a GPU; copies from it
+ * go through the runtime's pageable path).  hc_store_create is pinned = 1. */
+hc_status hc_store_create_ex(int32_t n_layers, int32_t d_model, int32_t chunk_tokens,
+                             int64_t capacity_chunks, int32_t pinned, hc_store** out);
+hc_status hc_store_destroy(hc_store* store);
+
+/* Append n_tok rows (h_rows: host bf16 [n_tok, d_model]) to (seq_id, layer).  Layers
+ * must not run ahead of the layer below them (HC_ESTATE).  HC_ERANGE when the arena is
+ * full.  Plain host memcpy. */
+hc_status hc_store_append(hc_store* store, int64_t seq_id, int32_t layer,
+                          const void* h_rows, int32_t n_tok);
+
+/* Tokens stored for (seq_id, layer); 0 for an unknown context. */
+int64_t hc_store_tokens(const hc_store* store, int64_t seq_id, int32_t layer);
+
+/* Read-side index: pointer to chunk `chunk` of (seq_id, layer) in pinned host memory and
+ * the number of valid rows in it. */
+hc_status hc_store_chunk(const hc_store* store, int64_t seq_id, int32_t layer,
+                         int32_t chunk, const void** h_ptr, int32_t* rows);
+
+/* Forget a context and return its chunks to the arena. */
+hc_status hc_store_drop(hc_store* store, int64_t seq_id);
+
+/* Restore ALL layers of tokens [tok_begin, tok_begin + n_tok) of one stored context,
+ * token i sitting at absolute position pos_offset + i (Section 3.1 pipeline; Section 5
+ * "Pipelined state transmission").  Per layer the chunks are copied to one of two HBM
+ * staging buffers with hipMemcpyAsync on `copy_stream`, and the restoration kernel runs
+ * on `compute_stream`; events order the two so that the transfer of layer L+1 overlaps
+ * the kernel of layer L.  Staging buffers are allocated inside the call when the
+ * context has none large enough.  Returns after everything is enqueued; the caller
+ * synchronises `compute_stream`.  The two streams must differ. */
+hc_status hc_restore_context(hc_ctx* ctx, const hc_store* store, int64_t seq_id,
+                             int32_t tok_begin, int32_t n_tok, int32_t pos_offset,
+                             const int32_t* d_block_table, int32_t n_blocks,
+                             void* compute_stream, void* copy_stream);
+
+/* ---- measurement hooks -------------------------------------------------------------
+ * Average duration in milliseconds of the restoration kernel launches queued on
+ * `stream` between hc_timing_begin and hc_timing_end, measured with HIP events on that
+ * stream around every launch of this context (at most 4096 launches are recorded).
+ * hc_timing_end synchronises the stream.  *out_launches receives the launch count. */
+hc_status hc_timing_begin(hc_ctx* ctx);
+hc_status hc_timing_end(hc_ctx* ctx, void* stream, double* out_avg_ms, int32_t* out_launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HCACHE_H */

@@ -1,0 +1,190 @@
+"""ctypes binding with the same names as include/hcache.h (argument marshalling only)."""
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_FILE = os.path.join(HERE, "libhcache.so")
+
+HC_OK, HC_EINVAL, HC_ERANGE, HC_EALIGN, HC_ENOMEM, HC_EHIP, HC_ESTATE = 0, -1, -2, -3, -4, -5, -6
+HC_DEV_BAD_POSITION, HC_DEV_BAD_PAGE = 1, 2
+_STATUS_NAMES = {0: "HC_OK", -1: "HC_EINVAL", -2: "HC_ERANGE", -3: "HC_EALIGN", -4: "HC_ENOMEM",
+                 -5: "HC_EHIP", -6: "HC_ESTATE"}
+
+
+class HCacheError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"{_STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+
+
+class ModelDesc(C.Structure):
+    """Mirror of hc_model_desc."""
+    _fields_ = [
+        ("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
+        ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("block_size", C.c_int32),
+        ("max_position", C.c_int32), ("rope_style", C.c_int32),
+        ("rope_theta", C.c_float), ("rms_eps", C.c_float),
+    ]
+
+
+def lib_path():
+    return _LIB_FILE
+
+
+def _load():
+    if not os.path.exists(_LIB_FILE):
+        raise ImportError(
+            f"{_LIB_FILE} is missing: build it with `python -m paper_2410_05004_amd.build` "
+            "(there is no CPU fallback for the restoration path)")
+    L = C.CDLL(_LIB_FILE)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    p = C.POINTER
+    sigs = {
+        "hc_last_error": (C.c_char_p, []),
+        "hc_version": (C.c_char_p, []),
+        "hc_validate_desc": (i32, [p(ModelDesc)]),
+        "hc_create": (i32, [p(ModelDesc), p(vp)]),
+        "hc_destroy": (i32, [vp]),
+        "hc_set_layer_weights": (i32, [vp, i32, vp, vp, vp]),
+        "hc_set_kv_pool": (i32, [vp, i32, vp, i64]),
+        "hc_restore_kv": (i32, [vp, i32, vp, vp, i32, vp, i32, vp]),
+        "hc_restore_kv_ragged": (i32, [vp, i32, vp, vp, i32, vp, i32, vp, i32, vp]),
+        "hc_poll_device_error": (i32, [vp, vp, p(i32)]),
+        "hc_store_create": (i32, [i32, i32, i32, i64, p(vp)]),
+        "hc_store_create_ex": (i32, [i32, i32, i32, i64, i32, p(vp)]),
+        "hc_store_destroy": (i32, [vp]),
+        "hc_store_append": (i32, [vp, i64, i32, vp, i32]),
+        "hc_store_tokens": (i64, [vp, i64, i32]),
+        "hc_store_chunk": (i32, [vp, i64, i32, i32, p(vp), p(i32)]),
+        "hc_store_drop": (i32, [vp, i64]),
+        "hc_restore_context": (i32, [vp, vp, i64, i32, i32, i32, vp, i32, vp, vp]),
+        "hc_timing_begin": (i32, [vp]),
+        "hc_timing_end": (i32, [vp, vp, p(C.c_double), p(i32)]),
+    }
+    for name, (res, args) in sigs.items():
+        fn = getattr(L, name)
+        fn.restype, fn.argtypes = res, args
+    return L
+
+
+lib = _load()
+EXPORTED = ("hc_last_error hc_version hc_validate_desc hc_create hc_destroy hc_set_layer_weights "
+            "hc_set_kv_pool hc_restore_kv hc_restore_kv_ragged hc_poll_device_error hc_store_create "
+            "hc_store_create_ex hc_store_destroy hc_store_append hc_store_tokens hc_store_chunk "
+            "hc_store_drop hc_restore_context hc_timing_begin hc_timing_end").split()
+
+
+def _check(status):
+    if status != HC_OK:
+        raise HCacheError(status, lib.hc_last_error().decode())
+
+
+def version():
+    return lib.hc_version().decode()
+
+
+def validate_desc(desc):
+    _check(lib.hc_validate_desc(C.byref(desc)))
+
+
+def _ptr(x):
+    """Address of a torch tensor / numpy array / int (None -> NULL)."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    return x.ctypes.data
+
+
+class Context:
+    """Owner of an hc_ctx*.  Methods carry the names of the C entry points."""
+
+    def __init__(self, desc):
+        self.desc = desc
+        h = C.c_void_p()
+        _check(lib.hc_create(C.byref(desc), C.byref(h)))
+        self._h = h
+
+    def destroy(self):
+        if self._h:
+            lib.hc_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def set_layer_weights(self, layer, d_wkv, d_gamma, stream=0):
+        _check(lib.hc_set_layer_weights(self._h, layer, _ptr(d_wkv), _ptr(d_gamma), stream))
+
+    def set_kv_pool(self, layer, d_pool, num_pages):
+        _check(lib.hc_set_kv_pool(self._h, layer, _ptr(d_pool), num_pages))
+
+    def restore_kv(self, layer, d_hidden, d_positions, n_tok, d_block_table, n_blocks, stream=0):
+        _check(lib.hc_restore_kv(self._h, layer, _ptr(d_hidden), _ptr(d_positions), n_tok,
+                                 _ptr(d_block_table), n_blocks, stream))
+
+    def restore_kv_ragged(self, layer, d_hidden, d_positions, total_tokens, d_cu_seqlens, n_seq,
+                          d_block_tables, max_blocks, stream=0):
+        _check(lib.hc_restore_kv_ragged(self._h, layer, _ptr(d_hidden), _ptr(d_positions),
+                                        total_tokens, _ptr(d_cu_seqlens), n_seq,
+                                        _ptr(d_block_tables), max_blocks, stream))
+
+    def poll_device_error(self, stream=0):
+        flags = C.c_int32(0)
+        _check(lib.hc_poll_device_error(self._h, stream, C.byref(flags)))
+        return flags.value
+
+    def restore_context(self, store, seq_id, tok_begin, n_tok, pos_offset, d_block_table, n_blocks,
+                        compute_stream, copy_stream):
+        _check(lib.hc_restore_context(self._h, store._h, seq_id, tok_begin, n_tok, pos_offset,
+                                      _ptr(d_block_table), n_blocks, compute_stream, copy_stream))
+
+    def timing_begin(self):
+        _check(lib.hc_timing_begin(self._h))
+
+    def timing_end(self, stream=0):
+        avg, n = C.c_double(0), C.c_int32(0)
+        _check(lib.hc_timing_end(self._h, stream, C.byref(avg), C.byref(n)))
+        return avg.value, n.value
+
+
+class Store:
+    """Owner of an hc_store*."""
+
+    def __init__(self, n_layers, d_model, chunk_tokens, capacity_chunks, pinned=True):
+        h = C.c_void_p()
+        _check(lib.hc_store_create_ex(n_layers, d_model, chunk_tokens, capacity_chunks,
+                                      1 if pinned else 0, C.byref(h)))
+        self._h = h
+        self.n_layers, self.d_model, self.chunk_tokens = n_layers, d_model, chunk_tokens
+
+    def destroy(self):
+        if self._h:
+            lib.hc_store_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def append(self, seq_id, layer, h_rows, n_tok):
+        _check(lib.hc_store_append(self._h, seq_id, layer, _ptr(h_rows), n_tok))
+
+    def tokens(self, seq_id, layer):
+        return lib.hc_store_tokens(self._h, seq_id, layer)
+
+    def chunk(self, seq_id, layer, chunk):
+        """(host address, valid rows) of one chunk."""
+        ptr, rows = C.c_void_p(), C.c_int32(0)
+        _check(lib.hc_store_chunk(self._h, seq_id, layer, chunk, C.byref(ptr), C.byref(rows)))
+        return ptr.value, rows.value
+
+    def drop(self, seq_id):
+        _check(lib.hc_store_drop(self._h, seq_id))

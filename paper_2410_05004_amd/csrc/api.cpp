@@ -1,0 +1,275 @@
+// C ABI of libhcache.so: argument validation, context state, launches.
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "hcache_internal.h"
+
+namespace hc {
+
+static thread_local std::string g_last_error;
+
+hc_status fail(hc_status code, const std::string& msg) {
+  g_last_error = msg;
+  return code;
+}
+hc_status fail_hip(hipError_t e, const char* what) {
+  g_last_error = std::string(what) + ": " + hipGetErrorString(e);
+  (void)hipGetLastError();   // clear the sticky error so the next call starts clean
+  return HC_EHIP;
+}
+void clear_error() { g_last_error.clear(); }
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+static hc_status check_desc(const hc_model_desc* d) {
+  if (!d) return fail(HC_EINVAL, "desc is null");
+  if (d->n_layers <= 0) return fail(HC_EINVAL, "n_layers must be positive");
+  if (d->d_model <= 0 || d->d_model % kTileK != 0)
+    return fail(HC_EINVAL, "d_model must be a positive multiple of 64");
+  if (d->head_dim <= 0 || d->head_dim % 64 != 0)
+    return fail(HC_EINVAL, "head_dim must be a positive multiple of 64");
+  if (d->n_kv_heads <= 0 || d->n_q_heads <= 0 || d->n_q_heads % d->n_kv_heads != 0)
+    return fail(HC_EINVAL, "n_q_heads must be a positive multiple of n_kv_heads");
+  if (!is_pow2(d->block_size)) return fail(HC_EINVAL, "block_size must be a power of two");
+  if (d->max_position <= 0) return fail(HC_EINVAL, "max_position must be positive");
+  if ((int64_t)d->max_position * (d->head_dim / 2) * 8 > ((int64_t)1 << 34))
+    return fail(HC_EINVAL, "RoPE table would exceed 16 GiB");
+  if (d->rope_style != 0 && d->rope_style != 1)
+    return fail(HC_EINVAL, "rope_style must be 0 (half-split) or 1 (interleaved)");
+  if (!(d->rope_theta > 0.f)) return fail(HC_EINVAL, "rope_theta must be positive");
+  if (!(d->rms_eps >= 0.f)) return fail(HC_EINVAL, "rms_eps must be non-negative");
+  if ((int64_t)d->n_kv_heads * d->head_dim > (1 << 20))
+    return fail(HC_EINVAL, "n_kv_heads * head_dim too large");
+  return HC_OK;
+}
+
+static hc_status check_layer(const hc_ctx* ctx, int32_t layer) {
+  if (!ctx) return fail(HC_EINVAL, "ctx is null");
+  if (layer < 0 || layer >= ctx->desc.n_layers) return fail(HC_ERANGE, "layer out of range");
+  return HC_OK;
+}
+
+// Launch the fused kernel for one layer (shared by the three restore entry points).
+hc_status restore_layer(hc_ctx* ctx, int32_t layer, const void* d_hidden,
+                        const int32_t* d_positions, int32_t pos_base, int32_t n_tok,
+                        const int32_t* d_cu, int32_t n_seq, const int32_t* d_tables,
+                        int32_t max_blocks, hipStream_t stream) {
+  const hc_layer_state& L = ctx->layers[layer];
+  if (!L.wpack) return fail(HC_ESTATE, "hc_set_layer_weights was not called for this layer");
+  if (!L.pool) return fail(HC_ESTATE, "hc_set_kv_pool was not called for this layer");
+  RestoreArgs a;
+  a.hidden = static_cast<const uint16_t*>(d_hidden);
+  a.wpack = L.wpack;
+  a.positions = d_positions;
+  a.cu_seqlens = d_cu;
+  a.block_tables = d_tables;
+  a.rope = ctx->rope;
+  a.pool = L.pool;
+  a.err = ctx->err_dev;
+  a.num_pages = L.num_pages;
+  a.pos_base = pos_base;
+  a.n_seq = n_seq;
+  a.max_blocks = max_blocks;
+  a.max_position = ctx->desc.max_position;
+  a.n_tok = n_tok;
+  a.d_model = ctx->desc.d_model;
+  a.d_kv = ctx->d_kv;
+  a.d_kv_pad = ctx->d_kv_pad;
+  a.head_dim = ctx->desc.head_dim;
+  a.block_shift = ctx->block_shift;
+  a.rope_style = ctx->desc.rope_style;
+  a.inv_d = 1.0f / (float)ctx->desc.d_model;
+  a.eps = ctx->desc.rms_eps;
+
+  const bool timed = ctx->timing && ctx->ev_used + 2 <= 8192;
+  if (timed) {
+    while ((int)ctx->ev_pool.size() < ctx->ev_used + 2) {
+      hipEvent_t e;
+      HC_HIP(hipEventCreate(&e));
+      ctx->ev_pool.push_back(e);
+    }
+    HC_HIP(hipEventRecord(ctx->ev_pool[ctx->ev_used], stream));
+  }
+  HC_HIP(launch_restore(a, stream));
+  if (timed) {
+    HC_HIP(hipEventRecord(ctx->ev_pool[ctx->ev_used + 1], stream));
+    ctx->ev_used += 2;
+  }
+  return HC_OK;
+}
+
+}  // namespace hc
+
+using namespace hc;
+
+extern "C" {
+
+const char* hc_last_error(void) { return g_last_error.c_str(); }
+const char* hc_version(void) { return "hcache-mi355x 0.1"; }
+
+hc_status hc_validate_desc(const hc_model_desc* desc) {
+  clear_error();
+  return check_desc(desc);
+}
+
+hc_status hc_create(const hc_model_desc* desc, hc_ctx** out) {
+  clear_error();
+  if (!out) return fail(HC_EINVAL, "out is null");
+  *out = nullptr;
+  hc_status s = check_desc(desc);
+  if (s != HC_OK) return s;
+  hc_ctx* ctx = new (std::nothrow) hc_ctx();
+  if (!ctx) return fail(HC_ENOMEM, "out of host memory");
+  ctx->desc = *desc;
+  ctx->d_kv = desc->n_kv_heads * desc->head_dim;
+  ctx->d_kv_pad = round_up(ctx->d_kv, kPartAlign);
+  ctx->n_phys = 2 * ctx->d_kv_pad;
+  for (int b = desc->block_size; b > 1; b >>= 1) ctx->block_shift++;
+  ctx->layers.resize(desc->n_layers);
+
+  hipError_t e = hipGetDevice(&ctx->device);
+  if (e == hipSuccess) e = configure_kernels();
+  if (e == hipSuccess)
+    e = hipMalloc(reinterpret_cast<void**>(&ctx->rope),
+                  (size_t)desc->max_position * (desc->head_dim / 2) * sizeof(float2));
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->err_dev), 256);
+  if (e == hipSuccess) e = hipMemset(ctx->err_dev, 0, 256);
+  if (e == hipSuccess)
+    e = launch_rope_table(ctx->rope, desc->max_position, desc->head_dim, (double)desc->rope_theta,
+                          nullptr);
+  if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+  if (e != hipSuccess) {
+    hc_status st = fail_hip(e, "hc_create");
+    if (ctx->rope) (void)hipFree(ctx->rope);
+    if (ctx->err_dev) (void)hipFree(ctx->err_dev);
+    delete ctx;
+    return st;
+  }
+  *out = ctx;
+  return HC_OK;
+}
+
+hc_status hc_destroy(hc_ctx* ctx) {
+  clear_error();
+  if (!ctx) return HC_OK;
+  (void)hipDeviceSynchronize();
+  for (auto& L : ctx->layers)
+    if (L.wpack) (void)hipFree(L.wpack);
+  if (ctx->rope) (void)hipFree(ctx->rope);
+  if (ctx->err_dev) (void)hipFree(ctx->err_dev);
+  for (int i = 0; i < 2; ++i) {
+    if (ctx->stage[i]) (void)hipFree(ctx->stage[i]);
+    if (ctx->h2d_done[i]) (void)hipEventDestroy(ctx->h2d_done[i]);
+    if (ctx->buf_free[i]) (void)hipEventDestroy(ctx->buf_free[i]);
+  }
+  for (hipEvent_t e : ctx->ev_pool) (void)hipEventDestroy(e);
+  delete ctx;
+  return HC_OK;
+}
+
+hc_status hc_set_layer_weights(hc_ctx* ctx, int32_t layer, const void* d_wkv, const void* d_gamma,
+                               void* stream) {
+  clear_error();
+  hc_status s = check_layer(ctx, layer);
+  if (s != HC_OK) return s;
+  if (!d_wkv || !d_gamma) return fail(HC_EINVAL, "weight pointer is null");
+  if (!aligned16(d_wkv) || !aligned16(d_gamma)) return fail(HC_EALIGN, "weights not 16-byte aligned");
+  hc_layer_state& L = ctx->layers[layer];
+  if (!L.wpack) {
+    const size_t bytes = (size_t)ctx->n_phys * ctx->desc.d_model * sizeof(uint16_t);
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&L.wpack), bytes);
+    if (e != hipSuccess) {
+      L.wpack = nullptr;
+      (void)hipGetLastError();
+      return fail(HC_ENOMEM, "device allocation of packed weights failed");
+    }
+  }
+  HC_HIP(launch_pack_weights(static_cast<const uint16_t*>(d_wkv),
+                             static_cast<const uint16_t*>(d_gamma), L.wpack, ctx->desc.d_model,
+                             ctx->d_kv, ctx->desc.head_dim, ctx->desc.rope_style,
+                             static_cast<hipStream_t>(stream)));
+  return HC_OK;
+}
+
+hc_status hc_set_kv_pool(hc_ctx* ctx, int32_t layer, void* d_pool, int64_t num_pages) {
+  clear_error();
+  hc_status s = check_layer(ctx, layer);
+  if (s != HC_OK) return s;
+  if (!d_pool) return fail(HC_EINVAL, "pool pointer is null");
+  if (!aligned16(d_pool)) return fail(HC_EALIGN, "pool not 16-byte aligned");
+  if (num_pages <= 0 || num_pages > ((int64_t)1 << 31) - 1)
+    return fail(HC_ERANGE, "num_pages out of range");
+  ctx->layers[layer].pool = static_cast<uint16_t*>(d_pool);
+  ctx->layers[layer].num_pages = num_pages;
+  return HC_OK;
+}
+
+hc_status hc_restore_kv(hc_ctx* ctx, int32_t layer, const void* d_hidden,
+                        const int32_t* d_positions, int32_t n_tok, const int32_t* d_block_table,
+                        int32_t n_blocks, void* stream) {
+  clear_error();
+  hc_status s = check_layer(ctx, layer);
+  if (s != HC_OK) return s;
+  if (n_tok < 0 || n_blocks < 0) return fail(HC_EINVAL, "negative size");
+  if (n_tok == 0) return HC_OK;
+  if (!d_hidden || !d_positions || !d_block_table) return fail(HC_EINVAL, "null device pointer");
+  if (!aligned16(d_hidden)) return fail(HC_EALIGN, "hidden not 16-byte aligned");
+  return restore_layer(ctx, layer, d_hidden, d_positions, 0, n_tok, nullptr, 1, d_block_table,
+                       n_blocks, static_cast<hipStream_t>(stream));
+}
+
+hc_status hc_restore_kv_ragged(hc_ctx* ctx, int32_t layer, const void* d_hidden,
+                               const int32_t* d_positions, int32_t h_total_tokens,
+                               const int32_t* d_cu_seqlens, int32_t n_seq,
+                               const int32_t* d_block_tables, int32_t max_blocks, void* stream) {
+  clear_error();
+  hc_status s = check_layer(ctx, layer);
+  if (s != HC_OK) return s;
+  if (h_total_tokens < 0 || n_seq < 0 || max_blocks < 0) return fail(HC_EINVAL, "negative size");
+  if (h_total_tokens == 0 || n_seq == 0) return HC_OK;
+  if (!d_hidden || !d_positions || !d_cu_seqlens || !d_block_tables)
+    return fail(HC_EINVAL, "null device pointer");
+  if (!aligned16(d_hidden)) return fail(HC_EALIGN, "hidden not 16-byte aligned");
+  return restore_layer(ctx, layer, d_hidden, d_positions, 0, h_total_tokens, d_cu_seqlens, n_seq,
+                       d_block_tables, max_blocks, static_cast<hipStream_t>(stream));
+}
+
+hc_status hc_poll_device_error(hc_ctx* ctx, void* stream, int32_t* out_flags) {
+  clear_error();
+  if (!ctx || !out_flags) return fail(HC_EINVAL, "null argument");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  HC_HIP(hipMemcpyAsync(out_flags, ctx->err_dev, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+  HC_HIP(hipMemsetAsync(ctx->err_dev, 0, sizeof(int32_t), st));
+  HC_HIP(hipStreamSynchronize(st));
+  return HC_OK;
+}
+
+hc_status hc_timing_begin(hc_ctx* ctx) {
+  clear_error();
+  if (!ctx) return fail(HC_EINVAL, "ctx is null");
+  ctx->timing = true;
+  ctx->ev_used = 0;
+  return HC_OK;
+}
+
+hc_status hc_timing_end(hc_ctx* ctx, void* stream, double* out_avg_ms, int32_t* out_launches) {
+  clear_error();
+  if (!ctx || !out_avg_ms || !out_launches) return fail(HC_EINVAL, "null argument");
+  ctx->timing = false;
+  HC_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  double total = 0.0;
+  const int n = ctx->ev_used / 2;
+  for (int i = 0; i < n; ++i) {
+    float ms = 0.f;
+    HC_HIP(hipEventElapsedTime(&ms, ctx->ev_pool[2 * i], ctx->ev_pool[2 * i + 1]));
+    total += ms;
+  }
+  *out_launches = n;
+  *out_avg_ms = n ? total / n : 0.0;
+  ctx->ev_used = 0;
+  return HC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,93 @@
+// One-time kernels: weight packing (per layer) and the RoPE (cos, sin) table (per context).
+#include "hcache_internal.h"
+
+namespace hc {
+
+// ---- weight packing -------------------------------------------------------------------
+// Physical row order of the packed weights [2 * d_kv_pad, d_model]:
+//   part   = K rows first (padded to a multiple of 128 rows with zeros), then V rows;
+//   inside a part, rows come in "pair groups" of 64: group G covers head G / (hd/64) and
+//   RoPE pair indices [32 qq, 32 qq + 32), qq = G % (hd/64).  The first 32 rows of a group
+//   are the first members of those pairs, the last 32 rows the second members
+//   (half-split: features i and i + hd/2; interleaved: features 2i and 2i + 1);
+//   inside a 32-row block, row i maps to pair offset u = 16*((i/4)%2) + 4*(i/8) + i%4,
+//   which is the order in which a lane of v_mfma_f32_32x32x16 receives its 16 outputs
+//   (register v of lane half g holds block row 8*(v/4) + 4*g + v%4), so that a lane ends
+//   up with 16 consecutive pair offsets.
+// Value: bf16( float(W[logical row][c]) * float(gamma[c]) ), one rounding.
+__device__ __forceinline__ int logical_row(int p, int d_kv, int d_kv_pad, int hd, int style) {
+  const int part = p >= d_kv_pad ? 1 : 0;
+  const int pp = p - part * d_kv_pad;
+  const int grp = pp >> 6;
+  if (grp * kPairGroup >= d_kv) return -1;                // padding
+  const int member = (pp >> 5) & 1, i = pp & 31;
+  const int u = 16 * ((i >> 2) & 1) + 4 * (i >> 3) + (i & 3);
+  const int gph = hd >> 6;
+  const int head = grp / gph, qq = grp - head * gph;
+  const int pair = 32 * qq + u;
+  const int f = style == 0 ? head * hd + member * (hd >> 1) + pair : head * hd + 2 * pair + member;
+  return part * d_kv + f;
+}
+
+__global__ __launch_bounds__(256) void pack_weights_kernel(const uint16_t* __restrict__ wkv,
+                                                           const uint16_t* __restrict__ gamma,
+                                                           uint16_t* __restrict__ wpack, int d_model,
+                                                           int d_kv, int d_kv_pad, int hd, int style) {
+  const int p = blockIdx.x;                               // physical row
+  const int src = logical_row(p, d_kv, d_kv_pad, hd, style);
+  for (int c = threadIdx.x; c < d_model; c += blockDim.x) {
+    uint16_t out = 0;
+    if (src >= 0) {
+      const float w = __uint_as_float((uint32_t)wkv[(size_t)src * d_model + c] << 16);
+      const float g = __uint_as_float((uint32_t)gamma[c] << 16);
+      const float prod = w * g;
+      uint32_t u = __float_as_uint(prod);
+      if ((u & 0x7fffffffu) > 0x7f800000u) {
+        out = 0x7fc0;                                     // NaN
+      } else {
+        u += 0x7fffu + ((u >> 16) & 1u);                  // round to nearest even
+        out = (uint16_t)(u >> 16);
+      }
+    }
+    wpack[(size_t)p * d_model + c] = out;
+  }
+}
+
+hipError_t launch_pack_weights(const uint16_t* wkv, const uint16_t* gamma, uint16_t* wpack,
+                               int d_model, int d_kv, int head_dim, int rope_style,
+                               hipStream_t stream) {
+  const int d_kv_pad = round_up(d_kv, kPartAlign);
+  hipLaunchKernelGGL(pack_weights_kernel, dim3(2 * d_kv_pad), dim3(256), 0, stream, wkv, gamma,
+                     wpack, d_model, d_kv, d_kv_pad, head_dim, rope_style);
+  return hipGetLastError();
+}
+
+// ---- RoPE table -----------------------------------------------------------------------
+// table[p][i] = (cos, sin)(p * theta^(-2i/hd)), evaluated in fp64 and rounded once to fp32:
+// an fp32 product p * inv_freq would already be off by ~2e-3 rad at position 32768.
+__global__ __launch_bounds__(256) void rope_table_kernel(float2* __restrict__ table,
+                                                         int max_position, int half, double theta,
+                                                         double inv_hd) {
+  const long n = (long)max_position * half;
+  for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < n;
+       e += (long)gridDim.x * blockDim.x) {
+    const int p = (int)(e / half), i = (int)(e - (long)p * half);
+    const double inv_freq = pow(theta, -2.0 * (double)i * inv_hd);
+    double s, c;
+    sincos((double)p * inv_freq, &s, &c);
+    table[e] = make_float2((float)c, (float)s);
+  }
+}
+
+hipError_t launch_rope_table(float2* table, int max_position, int head_dim, double theta,
+                             hipStream_t stream) {
+  const int half = head_dim / 2;
+  const long n = (long)max_position * half;
+  if (n == 0) return hipSuccess;
+  const int blocks = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+  hipLaunchKernelGGL(rope_table_kernel, dim3(blocks), dim3(256), 0, stream, table, max_position,
+                     half, theta, 1.0 / (double)head_dim);
+  return hipGetLastError();
+}
+
+}  // namespace hc

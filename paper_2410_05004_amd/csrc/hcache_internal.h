@@ -1,0 +1,107 @@
+// Internal declarations shared by the translation units of libhcache.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "hcache.h"
+
+namespace hc {
+
+// Tile geometry of the fused restoration kernel.  The weight matrix is re-ordered once
+// (hc_set_layer_weights) so that the kernel's accumulator registers come out in a
+// store-friendly order; the constants below define that order and are used by both the
+// packing kernel and the restoration kernel.
+constexpr int kPairGroup = 64;    // physical rows per RoPE pair group: 32 "first" + 32 "second" features
+constexpr int kPartAlign = 128;   // the K part and the V part are each padded to this many rows
+constexpr int kTileF = 256;       // physical weight rows (features) per workgroup
+constexpr int kTileT = 256;       // tokens per workgroup
+constexpr int kTileK = 64;        // d_model slice per main-loop step
+
+inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+// Arguments of one restoration launch (device pointers unless noted).
+struct RestoreArgs {
+  const uint16_t* hidden;        // bf16 [n_tok, d_model]
+  const uint16_t* wpack;         // bf16 [n_phys, d_model], packed order, gamma folded in
+  const int32_t* positions;      // [n_tok] or nullptr: position = pos_base + row
+  const int32_t* cu_seqlens;     // [n_seq + 1] or nullptr (single context)
+  const int32_t* block_tables;   // [n_seq][max_blocks]
+  const float2* rope;            // [max_position][head_dim/2] (cos, sin)
+  uint16_t* pool;                // bf16 [num_pages][2][block_size][n_kv_heads][head_dim]
+  int32_t* err;                  // sticky error word (device-visible host memory)
+  int64_t num_pages;
+  int32_t pos_base;
+  int32_t n_seq;
+  int32_t max_blocks;
+  int32_t max_position;
+  int32_t n_tok;
+  int32_t d_model;
+  int32_t d_kv;
+  int32_t d_kv_pad;              // d_kv rounded up to kPartAlign
+  int32_t head_dim;
+  int32_t block_shift;           // log2(block_size)
+  int32_t rope_style;
+  float inv_d;                   // 1 / d_model
+  float eps;
+};
+
+// Launchers implemented in the .hip files.  All are asynchronous on `stream`.
+hipError_t launch_restore(const RestoreArgs& a, hipStream_t stream);
+hipError_t launch_pack_weights(const uint16_t* wkv, const uint16_t* gamma, uint16_t* wpack,
+                               int d_model, int d_kv, int head_dim, int rope_style,
+                               hipStream_t stream);
+hipError_t launch_rope_table(float2* table, int max_position, int head_dim, double theta,
+                             hipStream_t stream);
+hipError_t configure_kernels();   // one-time function attributes (dynamic LDS size)
+
+// Error plumbing: thread-local message + status.
+hc_status fail(hc_status code, const std::string& msg);
+hc_status fail_hip(hipError_t e, const char* what);
+void clear_error();
+
+#define HC_HIP(call)                                         \
+  do {                                                       \
+    hipError_t e_ = (call);                                  \
+    if (e_ != hipSuccess) return ::hc::fail_hip(e_, #call);  \
+  } while (0)
+
+}  // namespace hc
+
+struct hc_ctx;
+namespace hc {
+// Validated launch of the fused kernel for one layer (shared by every restore entry point).
+// positions == nullptr means position = pos_base + row.
+hc_status restore_layer(hc_ctx* ctx, int32_t layer, const void* d_hidden,
+                        const int32_t* d_positions, int32_t pos_base, int32_t n_tok,
+                        const int32_t* d_cu, int32_t n_seq, const int32_t* d_tables,
+                        int32_t max_blocks, hipStream_t stream);
+}  // namespace hc
+
+struct hc_layer_state {
+  uint16_t* wpack = nullptr;     // owned
+  uint16_t* pool = nullptr;      // borrowed
+  int64_t num_pages = 0;
+};
+
+struct hc_ctx {
+  hc_model_desc desc;
+  int device = 0;
+  int d_kv = 0, d_kv_pad = 0, n_phys = 0, block_shift = 0;
+  float2* rope = nullptr;                 // owned, device
+  int32_t* err_host = nullptr;            // owned, pinned + mapped
+  int32_t* err_dev = nullptr;             // device view of err_host
+  std::vector<hc_layer_state> layers;
+  // staging for hc_restore_context
+  uint16_t* stage[2] = {nullptr, nullptr};
+  int64_t stage_tokens = 0;
+  hipEvent_t h2d_done[2] = {nullptr, nullptr};
+  hipEvent_t buf_free[2] = {nullptr, nullptr};
+  // per-launch timing
+  bool timing = false;
+  std::vector<hipEvent_t> ev_pool;        // created on demand, reused
+  int ev_used = 0;
+};

@@ -1,0 +1,247 @@
+// Host store of saved hidden states in fixed-size token chunks (paper Section 4.2.1),
+// and the pipelined whole-context restore that reads it (Section 3.1 pipeline, Section 5
+// "Pipelined state transmission").
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <unordered_map>
+
+#include "hcache_internal.h"
+
+struct hc_seq_state {
+  std::vector<std::vector<int64_t>> chunks;   // per layer: arena chunk slots, in token order
+  std::vector<int64_t> tokens;                // per layer: rows stored
+};
+
+struct hc_store {
+  int32_t n_layers = 0, d_model = 0, chunk_tokens = 0;
+  int64_t capacity_chunks = 0;
+  size_t row_bytes = 0, chunk_bytes = 0;
+  unsigned char* arena = nullptr;
+  bool pinned = false;
+  int64_t next_fresh = 0;                     // chunks [next_fresh, capacity) were never used
+  std::vector<int64_t> free_list;             // returned chunks, reused first
+  std::unordered_map<int64_t, hc_seq_state> seqs;
+};
+
+using namespace hc;
+
+extern "C" {
+
+hc_status hc_store_create_ex(int32_t n_layers, int32_t d_model, int32_t chunk_tokens,
+                             int64_t capacity_chunks, int32_t pinned, hc_store** out) {
+  clear_error();
+  if (!out) return fail(HC_EINVAL, "out is null");
+  *out = nullptr;
+  if (n_layers <= 0 || d_model <= 0 || chunk_tokens <= 0 || capacity_chunks <= 0)
+    return fail(HC_EINVAL, "store dimensions must be positive");
+  if (d_model % 8 != 0) return fail(HC_EINVAL, "d_model must be a multiple of 8 (16-byte rows)");
+  hc_store* st = new (std::nothrow) hc_store();
+  if (!st) return fail(HC_ENOMEM, "out of host memory");
+  st->n_layers = n_layers;
+  st->d_model = d_model;
+  st->chunk_tokens = chunk_tokens;
+  st->capacity_chunks = capacity_chunks;
+  st->row_bytes = (size_t)d_model * 2;
+  st->chunk_bytes = st->row_bytes * chunk_tokens;
+  const size_t bytes = st->chunk_bytes * (size_t)capacity_chunks;
+  if (pinned) {
+    void* p = nullptr;
+    hipError_t e = hipHostMalloc(&p, bytes, hipHostMallocDefault);
+    if (e != hipSuccess) {
+      delete st;
+      (void)hipGetLastError();
+      return fail(HC_ENOMEM, std::string("hipHostMalloc of the chunk arena failed: ") +
+                                 hipGetErrorString(e));
+    }
+    st->arena = static_cast<unsigned char*>(p);
+    st->pinned = true;
+  } else {
+    void* p = nullptr;
+    if (posix_memalign(&p, 4096, bytes) != 0) {
+      delete st;
+      return fail(HC_ENOMEM, "allocation of the chunk arena failed");
+    }
+    st->arena = static_cast<unsigned char*>(p);
+  }
+  *out = st;
+  return HC_OK;
+}
+
+hc_status hc_store_create(int32_t n_layers, int32_t d_model, int32_t chunk_tokens,
+                          int64_t capacity_chunks, hc_store** out) {
+  return hc_store_create_ex(n_layers, d_model, chunk_tokens, capacity_chunks, 1, out);
+}
+
+hc_status hc_store_destroy(hc_store* st) {
+  clear_error();
+  if (!st) return HC_OK;
+  if (st->arena) {
+    if (st->pinned) (void)hipHostFree(st->arena);
+    else free(st->arena);
+  }
+  delete st;
+  return HC_OK;
+}
+
+hc_status hc_store_append(hc_store* st, int64_t seq_id, int32_t layer, const void* h_rows,
+                          int32_t n_tok) {
+  clear_error();
+  if (!st) return fail(HC_EINVAL, "store is null");
+  if (layer < 0 || layer >= st->n_layers) return fail(HC_ERANGE, "layer out of range");
+  if (n_tok < 0) return fail(HC_EINVAL, "negative token count");
+  if (n_tok == 0) return HC_OK;
+  if (!h_rows) return fail(HC_EINVAL, "rows pointer is null");
+  auto it = st->seqs.find(seq_id);
+  if (it == st->seqs.end()) {
+    hc_seq_state s;
+    s.chunks.resize(st->n_layers);
+    s.tokens.assign(st->n_layers, 0);
+    it = st->seqs.emplace(seq_id, std::move(s)).first;
+  }
+  hc_seq_state& s = it->second;
+  // generation order: a layer never holds more tokens than the layer below it
+  if (layer > 0 && s.tokens[layer - 1] < s.tokens[layer] + n_tok)
+    return fail(HC_ESTATE, "layer appended before the layer below it (layer-before-token order)");
+  // make sure the arena can take the whole append before touching anything
+  const int64_t have = (int64_t)s.chunks[layer].size() * st->chunk_tokens - s.tokens[layer];
+  const int64_t need_rows = n_tok > have ? n_tok - have : 0;
+  const int64_t need_chunks = (need_rows + st->chunk_tokens - 1) / st->chunk_tokens;
+  const int64_t avail = (int64_t)st->free_list.size() + (st->capacity_chunks - st->next_fresh);
+  if (need_chunks > avail) return fail(HC_ERANGE, "chunk arena is full");
+
+  const unsigned char* src = static_cast<const unsigned char*>(h_rows);
+  int32_t left = n_tok;
+  while (left > 0) {
+    const int64_t fill = s.tokens[layer] % st->chunk_tokens;
+    if (fill == 0 && s.tokens[layer] == (int64_t)s.chunks[layer].size() * st->chunk_tokens) {
+      int64_t slot;
+      if (!st->free_list.empty()) {
+        slot = st->free_list.back();
+        st->free_list.pop_back();
+      } else {
+        slot = st->next_fresh++;
+      }
+      s.chunks[layer].push_back(slot);
+    }
+    const int64_t room = st->chunk_tokens - fill;
+    const int32_t take = left < room ? left : (int32_t)room;
+    unsigned char* dst = st->arena + (size_t)s.chunks[layer].back() * st->chunk_bytes +
+                         (size_t)fill * st->row_bytes;
+    memcpy(dst, src, (size_t)take * st->row_bytes);
+    src += (size_t)take * st->row_bytes;
+    s.tokens[layer] += take;
+    left -= take;
+  }
+  return HC_OK;
+}
+
+int64_t hc_store_tokens(const hc_store* st, int64_t seq_id, int32_t layer) {
+  if (!st || layer < 0 || layer >= st->n_layers) return 0;
+  auto it = st->seqs.find(seq_id);
+  return it == st->seqs.end() ? 0 : it->second.tokens[layer];
+}
+
+hc_status hc_store_chunk(const hc_store* st, int64_t seq_id, int32_t layer, int32_t chunk,
+                         const void** h_ptr, int32_t* rows) {
+  clear_error();
+  if (!st || !h_ptr || !rows) return fail(HC_EINVAL, "null argument");
+  if (layer < 0 || layer >= st->n_layers) return fail(HC_ERANGE, "layer out of range");
+  auto it = st->seqs.find(seq_id);
+  if (it == st->seqs.end()) return fail(HC_ERANGE, "unknown context");
+  const hc_seq_state& s = it->second;
+  if (chunk < 0 || chunk >= (int64_t)s.chunks[layer].size()) return fail(HC_ERANGE, "no such chunk");
+  const int64_t before = (int64_t)chunk * st->chunk_tokens;
+  const int64_t r = s.tokens[layer] - before;
+  *rows = (int32_t)(r < st->chunk_tokens ? r : st->chunk_tokens);
+  *h_ptr = st->arena + (size_t)s.chunks[layer][chunk] * st->chunk_bytes;
+  return HC_OK;
+}
+
+hc_status hc_store_drop(hc_store* st, int64_t seq_id) {
+  clear_error();
+  if (!st) return fail(HC_EINVAL, "store is null");
+  auto it = st->seqs.find(seq_id);
+  if (it == st->seqs.end()) return fail(HC_ERANGE, "unknown context");
+  for (auto& per_layer : it->second.chunks)
+    for (int64_t slot : per_layer) st->free_list.push_back(slot);
+  st->seqs.erase(it);
+  return HC_OK;
+}
+
+hc_status hc_restore_context(hc_ctx* ctx, const hc_store* st, int64_t seq_id, int32_t tok_begin,
+                             int32_t n_tok, int32_t pos_offset, const int32_t* d_block_table,
+                             int32_t n_blocks, void* compute_stream, void* copy_stream) {
+  clear_error();
+  if (!ctx || !st) return fail(HC_EINVAL, "null ctx or store");
+  if (st->n_layers != ctx->desc.n_layers || st->d_model != ctx->desc.d_model)
+    return fail(HC_EINVAL, "store and context disagree on n_layers / d_model");
+  if (tok_begin < 0 || n_tok < 0 || n_blocks < 0) return fail(HC_EINVAL, "negative size");
+  if (n_tok == 0) return HC_OK;
+  if (!d_block_table) return fail(HC_EINVAL, "block table is null");
+  if (compute_stream == copy_stream) return fail(HC_EINVAL, "compute and copy streams must differ");
+  auto it = st->seqs.find(seq_id);
+  if (it == st->seqs.end()) return fail(HC_ERANGE, "unknown context");
+  const hc_seq_state& s = it->second;
+  const int L = ctx->desc.n_layers;
+  for (int l = 0; l < L; ++l) {
+    if (s.tokens[l] < (int64_t)tok_begin + n_tok)
+      return fail(HC_ERANGE, "token range exceeds what the store holds for some layer");
+    if (!ctx->layers[l].wpack || !ctx->layers[l].pool)
+      return fail(HC_ESTATE, "weights or KV pool missing for some layer");
+  }
+  if ((int64_t)pos_offset + tok_begin + n_tok > ctx->desc.max_position || pos_offset < 0)
+    return fail(HC_ERANGE, "positions exceed max_position");
+  hipStream_t cs = static_cast<hipStream_t>(compute_stream);
+  hipStream_t xs = static_cast<hipStream_t>(copy_stream);
+
+  // staging buffers and events
+  if (ctx->stage_tokens < n_tok) {
+    for (int b = 0; b < 2; ++b) {
+      if (ctx->stage[b]) { HC_HIP(hipFree(ctx->stage[b])); ctx->stage[b] = nullptr; }
+    }
+    ctx->stage_tokens = 0;
+    for (int b = 0; b < 2; ++b) {
+      hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->stage[b]), (size_t)n_tok * st->row_bytes);
+      if (e != hipSuccess) {
+        (void)hipGetLastError();
+        ctx->stage[b] = nullptr;
+        return fail(HC_ENOMEM, "device allocation of a staging buffer failed");
+      }
+    }
+    ctx->stage_tokens = n_tok;
+  }
+  for (int b = 0; b < 2; ++b) {
+    if (!ctx->h2d_done[b]) HC_HIP(hipEventCreateWithFlags(&ctx->h2d_done[b], hipEventDisableTiming));
+    if (!ctx->buf_free[b]) {
+      HC_HIP(hipEventCreateWithFlags(&ctx->buf_free[b], hipEventDisableTiming));
+      HC_HIP(hipEventRecord(ctx->buf_free[b], cs));   // nothing uses the buffer yet
+    }
+  }
+
+  const int CT = st->chunk_tokens;
+  const int c_first = tok_begin / CT, c_last = (tok_begin + n_tok - 1) / CT;
+  for (int l = 0; l < L; ++l) {
+    const int b = l & 1;
+    // the kernel that last read stage[b] (two layers ago, or a previous call) must be done
+    HC_HIP(hipStreamWaitEvent(xs, ctx->buf_free[b], 0));
+    for (int c = c_first; c <= c_last; ++c) {
+      const int lo = c == c_first ? tok_begin - c * CT : 0;
+      const int hi = c == c_last ? tok_begin + n_tok - c * CT : CT;
+      const unsigned char* src = st->arena + (size_t)s.chunks[l][c] * st->chunk_bytes +
+                                 (size_t)lo * st->row_bytes;
+      unsigned char* dst = reinterpret_cast<unsigned char*>(ctx->stage[b]) +
+                           (size_t)(c * CT + lo - tok_begin) * st->row_bytes;
+      HC_HIP(hipMemcpyAsync(dst, src, (size_t)(hi - lo) * st->row_bytes, hipMemcpyHostToDevice, xs));
+    }
+    HC_HIP(hipEventRecord(ctx->h2d_done[b], xs));
+    HC_HIP(hipStreamWaitEvent(cs, ctx->h2d_done[b], 0));
+    hc_status r = restore_layer(ctx, l, ctx->stage[b], nullptr, pos_offset + tok_begin, n_tok,
+                                nullptr, 1, d_block_table, n_blocks, cs);
+    if (r != HC_OK) return r;
+    HC_HIP(hipEventRecord(ctx->buf_free[b], cs));
+  }
+  return HC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,266 @@
+"""GPU parity: the HIP restoration path, called through the C ABI, against the fp64 oracle
+on the same seeded inputs.  Indexing (which page/slot is written) must match exactly;
+values must agree within 2e-2 x the oracle's per-head RMS (bf16 inputs, fp32 accumulation,
+one bf16 rounding of the output)."""
+import numpy as np
+import pytest
+
+import synthetic as syn
+import oracle.hcache_oracle as oracle
+import gpu_harness as gh
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hc():
+    import paper_2410_05004_amd as hc
+    return hc
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    return torch
+
+
+def run_single(hc, torch, case, desc, positions, block_table, num_pages, layer=0):
+    ctx = hc.Context(desc)
+    pool = gh.new_pool(num_pages, desc.block_size, desc.n_kv_heads, desc.head_dim)
+    s = gh.stream_handle()
+    d_w, d_g = gh.to_dev_bf16(case.wkv_bits), gh.to_dev_bf16(case.gamma_bits)
+    ctx.set_layer_weights(layer, d_w, d_g, s)
+    ctx.set_kv_pool(layer, pool, num_pages)
+    d_x = gh.to_dev_bf16(case.x_bits) if len(case.x_bits) else None
+    d_pos, d_bt = gh.to_dev_i32(positions), gh.to_dev_i32(block_table)
+    ctx.restore_kv(layer, d_x, d_pos, len(positions), d_bt, len(block_table), s)
+    flags = ctx.poll_device_error(s)
+    bits = gh.pool_bits(pool)
+    ctx.destroy()
+    return bits, flags
+
+
+def oracle_single(case, desc, positions, block_table, num_pages):
+    pool = np.full((num_pages, 2, desc.block_size, desc.n_kv_heads, desc.head_dim), np.nan)
+    oracle.restore_kv(pool, case.x, case.gamma, case.wkv, positions, block_table,
+                      **gh.oracle_kw(desc))
+    return pool
+
+
+# ---------------------------------------------------------------------------------------
+def test_tiny_workload_all_layers(hc, torch):
+    """Workload 0 (2 layers, d=256, 4 KV heads of 64, T=128), every element."""
+    w = syn.WORKLOADS[0]
+    desc = gh.desc_of_workload(hc, w)
+    ctx = hc.Context(desc)
+    s = gh.stream_handle()
+    bt, num_pages = syn.block_table(w, w.tokens)
+    pos = np.arange(w.tokens, dtype=np.int32)
+    d_pos, d_bt = gh.to_dev_i32(pos), gh.to_dev_i32(bt)
+    keep = []
+    for l in range(w.n_layers):
+        wkv, gamma = syn.layer_weights(w, l)
+        x = syn.layer_hidden(w, l)
+        pool = gh.new_pool(num_pages, w.block_size, w.n_kv_heads, w.head_dim)
+        d_w, d_g, d_x = gh.to_dev_bf16(wkv), gh.to_dev_bf16(gamma), gh.to_dev_bf16(x)
+        keep += [d_w, d_g, d_x]
+        ctx.set_layer_weights(l, d_w, d_g, s)
+        ctx.set_kv_pool(l, pool, num_pages)
+        ctx.restore_kv(l, d_x, d_pos, w.tokens, d_bt, len(bt), s)
+        assert ctx.poll_device_error(s) == 0
+        ora = np.full((num_pages, 2, w.block_size, w.n_kv_heads, w.head_dim), np.nan)
+        oracle.restore_kv(ora, syn.bf16_bits_to_f64(x), syn.bf16_bits_to_f64(gamma),
+                          syn.bf16_bits_to_f64(wkv), pos, bt, **gh.oracle_kw(desc))
+        worst = gh.compare_pool(gh.pool_bits(pool), ora)
+        print(f"layer {l}: worst err = {worst * gh.TOL:.3e} x RMS_head")
+    ctx.destroy()
+
+
+SHAPES = [
+    # d_model, n_kv, hd, n_tok, style   (several token tiles + ragged tail; padded feature tiles)
+    (1024, 6, 128, 600, 0),
+    (512, 3, 64, 257, 0),      # d_kv = 192 -> part padded to 256 rows
+    (512, 3, 64, 300, 1),      # interleaved RoPE
+    (1024, 4, 128, 513, 1),
+    (256, 1, 64, 1, 0),        # a single token, a single head
+    (2048, 2, 128, 255, 0),
+]
+
+
+@pytest.mark.parametrize("d_model,n_kv,hd,n_tok,style", SHAPES)
+def test_shapes_against_oracle(hc, torch, d_model, n_kv, hd, n_tok, style):
+    rng = np.random.default_rng([11, d_model, n_kv, hd, n_tok, style])
+    case = gh.LayerCase(rng, d_model, n_kv, hd, n_tok)
+    B = 16
+    offset = 1000                                   # starts mid-page: 1000 = 62*16 + 8
+    n_blocks = (offset + n_tok + B - 1) // B
+    num_pages = n_blocks + 7
+    bt = rng.permutation(num_pages)[:n_blocks].astype(np.int32)
+    # tokens in scrambled order: positions drive RoPE and the slot, not the row index
+    pos = (offset + rng.permutation(n_tok)).astype(np.int32)
+    desc = gh.make_desc(hc, n_layers=1, d_model=d_model, n_q_heads=n_kv * 2, n_kv_heads=n_kv,
+                        head_dim=hd, block_size=B, max_position=offset + n_tok, rope_style=style,
+                        rope_theta=500000.0)
+    bits, flags = run_single(hc, torch, case, desc, pos, bt, num_pages)
+    assert flags == 0
+    worst = gh.compare_pool(bits, oracle_single(case, desc, pos, bt, num_pages))
+    print(f"worst err = {worst * gh.TOL:.3e} x RMS_head")
+
+
+def test_block_sizes(hc, torch):
+    for B in (8, 32):
+        rng = np.random.default_rng([5, B])
+        case = gh.LayerCase(rng, 512, 2, 128, 100)
+        n_blocks = (100 + B - 1) // B
+        bt = rng.permutation(n_blocks + 3)[:n_blocks].astype(np.int32)
+        pos = np.arange(100, dtype=np.int32)
+        desc = gh.make_desc(hc, n_layers=1, d_model=512, n_q_heads=2, n_kv_heads=2, head_dim=128,
+                            block_size=B, max_position=128)
+        bits, flags = run_single(hc, torch, case, desc, pos, bt, n_blocks + 3)
+        assert flags == 0
+        gh.compare_pool(bits, oracle_single(case, desc, pos, bt, n_blocks + 3))
+
+
+def test_ragged_batch(hc, torch):
+    rng = np.random.default_rng(17)
+    d_model, n_kv, hd, B = 512, 2, 128, 16
+    lens = np.array([37, 260, 1, 129, 300], dtype=np.int32)     # crosses token tiles mid-context
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T = int(cu[-1])
+    case = gh.LayerCase(rng, d_model, n_kv, hd, T)
+    pos = np.concatenate([np.arange(n) for n in lens]).astype(np.int32)
+    nblk = (lens + B - 1) // B
+    num_pages = int(nblk.sum()) + 9
+    perm = rng.permutation(num_pages).astype(np.int32)
+    tables = np.full((len(lens), int(nblk.max())), -1, dtype=np.int32)
+    at = 0
+    for s, n in enumerate(nblk):
+        tables[s, :n] = perm[at:at + n]
+        at += n
+    desc = gh.make_desc(hc, n_layers=1, d_model=d_model, n_q_heads=n_kv, n_kv_heads=n_kv,
+                        head_dim=hd, block_size=B, max_position=512)
+    ctx = hc.Context(desc)
+    s = gh.stream_handle()
+    pool = gh.new_pool(num_pages, B, n_kv, hd)
+    d_w, d_g, d_x = gh.to_dev_bf16(case.wkv_bits), gh.to_dev_bf16(case.gamma_bits), gh.to_dev_bf16(case.x_bits)
+    ctx.set_layer_weights(0, d_w, d_g, s)
+    ctx.set_kv_pool(0, pool, num_pages)
+    d_pos, d_cu, d_tab = gh.to_dev_i32(pos), gh.to_dev_i32(cu), gh.to_dev_i32(tables)
+    ctx.restore_kv_ragged(0, d_x, d_pos, T, d_cu, len(lens), d_tab, tables.shape[1], s)
+    assert ctx.poll_device_error(s) == 0
+    ora = np.full((num_pages, 2, B, n_kv, hd), np.nan)
+    oracle.restore_kv_ragged(ora, case.x, case.gamma, case.wkv, pos, cu, tables, **gh.oracle_kw(desc))
+    gh.compare_pool(gh.pool_bits(pool), ora)
+    ctx.destroy()
+
+
+def test_bad_rows_are_skipped_and_flagged(hc, torch):
+    rng = np.random.default_rng(23)
+    d_model, n_kv, hd, B, T = 256, 1, 64, 16, 40
+    case = gh.LayerCase(rng, d_model, n_kv, hd, T)
+    bt = np.array([3, -1, 1, 9], dtype=np.int32)     # block 1 unmapped, block 3 -> page outside pool
+    num_pages = 5
+    pos = np.arange(T, dtype=np.int32)               # 0..39 : blocks 0,1,2
+    pos[5] = 70                                      # beyond the block table (block 4)
+    pos[6] = -3
+    pos[7] = 48                                      # block 3 -> page 9 >= num_pages
+    desc = gh.make_desc(hc, n_layers=1, d_model=d_model, n_q_heads=1, n_kv_heads=1, head_dim=hd,
+                        block_size=B, max_position=128)
+    bits, flags = run_single(hc, torch, case, desc, pos, bt, num_pages)
+    assert flags == (hc.HC_DEV_BAD_POSITION | hc.HC_DEV_BAD_PAGE)
+    good = np.array([p >= 0 and p // B < 4 and 0 <= bt[p // B] < num_pages for p in pos])
+    ora = np.full((num_pages, 2, B, n_kv, hd), np.nan)
+    oracle.restore_kv(ora, case.x[good], case.gamma, case.wkv, pos[good], bt, **gh.oracle_kw(desc))
+    gh.compare_pool(bits, ora)
+    # position >= max_position is refused even when the table would cover it
+    desc2 = gh.make_desc(hc, n_layers=1, d_model=d_model, n_q_heads=1, n_kv_heads=1, head_dim=hd,
+                         block_size=B, max_position=16)
+    bits, flags = run_single(hc, torch, case, desc2, np.arange(T, dtype=np.int32),
+                             np.array([0, 1, 2], dtype=np.int32), num_pages)
+    assert flags == hc.HC_DEV_BAD_POSITION
+    assert np.all(bits[1:] == gh.SENTINEL) and np.all(bits[0] != gh.SENTINEL)
+
+
+def test_host_side_errors(hc, torch):
+    desc = gh.make_desc(hc, n_layers=2, d_model=256, n_q_heads=1, n_kv_heads=1, head_dim=64)
+    ctx = hc.Context(desc)
+    s = gh.stream_handle()
+    x = torch.zeros(64, 256, dtype=torch.bfloat16, device="cuda")
+    pos = torch.zeros(64, dtype=torch.int32, device="cuda")
+    bt = torch.zeros(8, dtype=torch.int32, device="cuda")
+
+    def status(fn, *a):
+        with pytest.raises(hc.HCacheError) as e:
+            fn(*a)
+        return e.value.status
+
+    assert status(ctx.restore_kv, 5, x, pos, 64, bt, 8, s) == hc.HC_ERANGE
+    assert status(ctx.restore_kv, 0, x, pos, 64, bt, 8, s) == hc.HC_ESTATE      # no weights yet
+    w = torch.zeros(128, 256, dtype=torch.bfloat16, device="cuda")
+    g = torch.ones(256, dtype=torch.bfloat16, device="cuda")
+    ctx.set_layer_weights(0, w, g, s)
+    assert status(ctx.restore_kv, 0, x, pos, 64, bt, 8, s) == hc.HC_ESTATE      # no pool yet
+    pool = gh.new_pool(4, 16, 1, 64)
+    ctx.set_kv_pool(0, pool, 4)
+    assert status(ctx.restore_kv, 0, None, pos, 64, bt, 8, s) == hc.HC_EINVAL
+    assert status(ctx.restore_kv, 0, x.data_ptr() + 2, pos, 63, bt, 8, s) == hc.HC_EALIGN
+    assert status(ctx.restore_kv, 0, x, pos, -1, bt, 8, s) == hc.HC_EINVAL
+    assert status(ctx.set_kv_pool, 0, pool, 0) == hc.HC_ERANGE
+    assert status(ctx.set_layer_weights, 0, None, g, s) == hc.HC_EINVAL
+    ctx.restore_kv(0, x, pos, 0, bt, 8, s)                                      # empty: no-op
+    assert ctx.poll_device_error(s) == 0
+    assert np.all(gh.pool_bits(pool) == gh.SENTINEL)
+    ctx.destroy()
+
+
+def test_restore_context_from_store(hc, torch):
+    """Whole-context pipelined restore from the pinned chunk store: all layers, a token range
+    that starts and ends inside chunks, positions offset so the first page is part filled."""
+    rng = np.random.default_rng(31)
+    L, d_model, n_kv, hd, B, CT = 5, 512, 2, 128, 16, 64
+    T_stored, tok_begin, n_tok, pos_offset = 700, 30, 650, 1000
+    desc = gh.make_desc(hc, n_layers=L, d_model=d_model, n_q_heads=n_kv, n_kv_heads=n_kv,
+                        head_dim=hd, block_size=B, max_position=pos_offset + T_stored)
+    cases = [gh.LayerCase(np.random.default_rng([31, l]), d_model, n_kv, hd, T_stored) for l in range(L)]
+    store = hc.Store(L, d_model, CT, capacity_chunks=L * ((T_stored + CT - 1) // CT) + 2, pinned=True)
+    # save order: a 512-token prefill, then smaller appends, layer by layer each time
+    cuts = [0, 512, 600, 601, 700]
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        for l in range(L):
+            store.append(3, l, np.ascontiguousarray(cases[l].x_bits[a:b]), b - a)
+    n_blocks = (pos_offset + T_stored + B - 1) // B
+    num_pages = n_blocks + 5
+    bt = rng.permutation(num_pages)[:n_blocks].astype(np.int32)
+    ctx = hc.Context(desc)
+    s = gh.stream_handle()
+    copy_stream = torch.cuda.Stream()
+    pools, keep = [], []
+    for l in range(L):
+        d_w, d_g = gh.to_dev_bf16(cases[l].wkv_bits), gh.to_dev_bf16(cases[l].gamma_bits)
+        keep += [d_w, d_g]
+        ctx.set_layer_weights(l, d_w, d_g, s)
+        pools.append(gh.new_pool(num_pages, B, n_kv, hd))
+        ctx.set_kv_pool(l, pools[l], num_pages)
+    d_bt = gh.to_dev_i32(bt)
+    torch.cuda.synchronize()
+    for rep in range(2):                                # second call reuses the staging buffers
+        ctx.restore_context(store, 3, tok_begin, n_tok, pos_offset, d_bt, n_blocks, s,
+                            copy_stream.cuda_stream)
+    assert ctx.poll_device_error(s) == 0
+    torch.cuda.synchronize()
+    pos = (pos_offset + tok_begin + np.arange(n_tok)).astype(np.int32)
+    for l in range(L):
+        ora = np.full((num_pages, 2, B, n_kv, hd), np.nan)
+        c = cases[l]
+        oracle.restore_kv(ora, c.x[tok_begin:tok_begin + n_tok], c.gamma, c.wkv, pos, bt,
+                          **gh.oracle_kw(desc))
+        gh.compare_pool(gh.pool_bits(pools[l]), ora)
+    # errors
+    with pytest.raises(hc.HCacheError) as e:
+        ctx.restore_context(store, 3, 100, 700, 0, d_bt, n_blocks, s, copy_stream.cuda_stream)
+    assert e.value.status == hc.HC_ERANGE
+    with pytest.raises(hc.HCacheError) as e:
+        ctx.restore_context(store, 3, 0, 10, 0, d_bt, n_blocks, s, s)
+    assert e.value.status == hc.HC_EINVAL
+    ctx.destroy()
+    store.destroy()

@@ -1,0 +1,138 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every symbol the
+header declares, validates descriptors, and its chunk store matches the oracle's model."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle.hcache_oracle as oracle
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def hc():
+    import paper_2410_05004_amd as hc
+    return hc
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "hcache.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hc_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(hc):
+    syms = header_symbols()
+    assert len(syms) >= 18
+    for s in syms:
+        assert hasattr(hc.lib, s), f"{s} declared in hcache.h but not exported"
+    from paper_2410_05004_amd.binding import EXPORTED
+    assert sorted(EXPORTED) == syms, "binding and header disagree on the entry points"
+
+
+def test_version_and_error_string(hc):
+    assert hc.version().startswith("hcache-mi355x")
+    assert hc.lib.hc_last_error() is not None
+
+
+def good_desc(hc, **over):
+    kw = dict(n_layers=2, d_model=256, n_q_heads=4, n_kv_heads=4, head_dim=64, block_size=16,
+              max_position=128, rope_style=0, rope_theta=10000.0, rms_eps=1e-5)
+    kw.update(over)
+    return hc.ModelDesc(*[kw[k] for k in ("n_layers", "d_model", "n_q_heads", "n_kv_heads",
+                                           "head_dim", "block_size", "max_position", "rope_style",
+                                           "rope_theta", "rms_eps")])
+
+
+def test_desc_validation(hc):
+    hc.validate_desc(good_desc(hc))
+    bad = [dict(n_layers=0), dict(d_model=100), dict(head_dim=48), dict(n_q_heads=6, n_kv_heads=4),
+           dict(block_size=12), dict(max_position=0), dict(rope_style=2), dict(rope_theta=0.0),
+           dict(rms_eps=-1.0), dict(n_kv_heads=0)]
+    for over in bad:
+        with pytest.raises(hc.HCacheError) as e:
+            hc.validate_desc(good_desc(hc, **over))
+        assert e.value.status == hc.HC_EINVAL, over
+        assert str(e.value)
+
+
+def read_chunk(store, seq, layer, c, d):
+    import ctypes
+    ptr, rows = store.chunk(seq, layer, c)
+    buf = (ctypes.c_uint16 * (rows * d)).from_address(ptr)
+    return np.frombuffer(buf, dtype=np.uint16).reshape(rows, d).copy()
+
+
+def test_store_matches_oracle_model(hc):
+    L, d, CT, T = 3, 16, 4, 11
+    st = hc.Store(L, d, CT, capacity_chunks=64, pinned=False)
+    ref = oracle.ChunkStore(L, d, CT)
+    rng = np.random.default_rng(1)
+    full = rng.integers(0, 65536, size=(L, T, d), dtype=np.uint16)
+    # generation order: prefill of 5 tokens, then token by token, layer by layer
+    steps = [(0, 5)] + [(t, t + 1) for t in range(5, T)]
+    for a, b in steps:
+        for l in range(L):
+            rows = np.ascontiguousarray(full[l, a:b])
+            st.append(7, l, rows, b - a)
+            ref.append(7, l, rows)
+    for l in range(L):
+        assert st.tokens(7, l) == T == ref.n_tokens(7, l)
+        for c in range(ref.n_chunks(7, l)):
+            assert np.array_equal(read_chunk(st, 7, l, c, d), ref.chunk(7, l, c))
+        with pytest.raises(hc.HCacheError) as e:
+            st.chunk(7, l, ref.n_chunks(7, l))
+        assert e.value.status == hc.HC_ERANGE
+    # Figure 6: 2nd token, 2nd layer -> chunk (layer 1, 0), row 1
+    assert np.array_equal(read_chunk(st, 7, 1, 0, d)[1], full[1, 1])
+    # chunks are taken from the arena in arrival order: the 5-token prefill fills two
+    # chunks of layer 0, then two of layer 1, then two of layer 2
+    p = [st.chunk(7, l, 0)[0] for l in range(L)]
+    assert p[1] - p[0] == 2 * CT * d * 2 and p[2] - p[1] == 2 * CT * d * 2
+    assert st.chunk(7, 0, 1)[0] - p[0] == CT * d * 2
+    st.destroy()
+
+
+def test_store_errors_and_reuse(hc):
+    L, d, CT = 2, 8, 4
+    st = hc.Store(L, d, CT, capacity_chunks=4, pinned=False)
+    rows = np.zeros((8, d), dtype=np.uint16)
+    with pytest.raises(hc.HCacheError) as e:        # layer 1 before layer 0
+        st.append(1, 1, rows, 1)
+    assert e.value.status == hc.HC_ESTATE
+    with pytest.raises(hc.HCacheError) as e:
+        st.append(1, 2, rows, 1)
+    assert e.value.status == hc.HC_ERANGE
+    st.append(1, 0, rows, 8)                        # 2 chunks
+    st.append(1, 1, rows, 8)                        # 2 chunks -> arena full
+    with pytest.raises(hc.HCacheError) as e:
+        st.append(2, 0, rows, 1)
+    assert e.value.status == hc.HC_ERANGE
+    assert st.tokens(2, 0) == 0
+    with pytest.raises(hc.HCacheError):
+        st.drop(99)
+    st.drop(1)
+    assert st.tokens(1, 0) == 0
+    st.append(2, 0, rows, 5)                        # reuses freed chunks
+    assert st.tokens(2, 0) == 5
+    assert st.chunk(2, 0, 1)[1] == 1                # tail chunk holds one row
+    st.append(2, 0, rows, 0)                        # empty append is a no-op
+    st.destroy()
+
+
+def test_store_bad_arguments(hc):
+    for args in [(0, 8, 4, 4), (2, 0, 4, 4), (2, 8, 0, 4), (2, 8, 4, 0), (2, 12, 4, 4)]:
+        with pytest.raises(hc.HCacheError) as e:
+            hc.Store(*args, pinned=False)
+        assert e.value.status == hc.HC_EINVAL
+
+
+def test_create_fails_loudly_without_gpu(hc):
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(hc.HCacheError) as e:
+        hc.Context(good_desc(hc))
+    assert e.value.status == hc.HC_EHIP
