@@ -26,7 +26,7 @@ static bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 static hc_status check_desc(const hc_model_desc* d) {
   if (!d) return fail(HC_EINVAL, "desc is null");
   if (d->n_layers <= 0) return fail(HC_EINVAL, "n_layers must be positive");
-  if (d->d_model <= 0 || d->d_model % kTileK != 0)
+  if (d->d_model <= 0 || d->d_model % 64 != 0)
     return fail(HC_EINVAL, "d_model must be a positive multiple of 64");
   if (d->head_dim <= 0 || d->head_dim % 64 != 0)
     return fail(HC_EINVAL, "head_dim must be a positive multiple of 64");

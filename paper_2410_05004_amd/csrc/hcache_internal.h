@@ -19,7 +19,7 @@ constexpr int kPairGroup = 64;    // physical rows per RoPE pair group: 32 "firs
 constexpr int kPartAlign = 128;   // the K part and the V part are each padded to this many rows
 constexpr int kTileF = 256;       // physical weight rows (features) per workgroup
 constexpr int kTileT = 256;       // tokens per workgroup
-constexpr int kTileK = 64;        // d_model slice per main-loop step
+constexpr int kTileK = 32;        // d_model slice per main-loop step
 
 inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 

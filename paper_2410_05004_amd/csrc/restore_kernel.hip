@@ -19,10 +19,11 @@
 //
 // Tiling.  Workgroup = 256 threads = 4 waves in a 2x2 arrangement; workgroup tile =
 // 256 features x 256 tokens, wave tile = 128 x 128 (4x4 MFMA blocks, 256 accumulator
-// registers).  The d_model loop advances 64 channels per step through two LDS stages of
-// 64 KiB (32 KiB weights + 32 KiB activations); rows are 128 bytes and their 16-byte
-// chunks are XOR-swizzled so that both the 16-byte LDS writes and the ds_read_b128
-// fragment reads are bank-conflict free.
+// registers).  The d_model loop advances 32 channels per step through a ring of four LDS
+// stages of 32 KiB (16 KiB weights + 16 KiB activations) filled by direct global->LDS
+// loads issued four tiles ahead; rows are 64 bytes and their 16-byte chunks are
+// XOR-swizzled (on the global address side, since a direct load fills LDS lane by lane)
+// so that the ds_read_b128 fragment reads are bank-conflict free.
 #include "hcache_internal.h"
 
 namespace hc {
@@ -34,13 +35,17 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 
 constexpr int kThreads = 256;
-constexpr int kRowBytes = kTileK * 2;                    // 128
-constexpr int kOperandBytes = 256 * kRowBytes;           // 32 KiB per operand per stage
-constexpr int kStageBytes = 2 * kOperandBytes;           // 64 KiB
-constexpr int kLdsBytes = 2 * kStageBytes;               // 128 KiB
+constexpr int kStages = 4;                               // LDS ring depth (tiles in flight)
+constexpr int kRowBytes = kTileK * 2;                    // 64
+constexpr int kOperandBytes = 256 * kRowBytes;           // 16 KiB per operand per stage
+constexpr int kStageBytes = 2 * kOperandBytes;           // 32 KiB
+constexpr int kLdsBytes = kStages * kStageBytes;         // 128 KiB
+static_assert(kTileK == 32, "the waitcnt constants below assume 8 direct loads per thread per tile");
 
-// 16-byte chunk `chunk` (0..7) of LDS row `row` lives at chunk position chunk ^ f(row).
-__device__ __forceinline__ int swizzle_of_row(int row) { return (row ^ (row >> 3)) & 7; }
+// 16-byte chunk `chunk` (0..3) of LDS row `row` lives at chunk position chunk ^ f(row); f is
+// chosen so that the 16 (or 8) consecutive rows one ds_read_b128 pass touches fall into
+// distinct banks whether the LDS serves 64 or 32 banks per clock.
+__device__ __forceinline__ int swizzle_of_row(int row) { return ((row >> 1) ^ (row >> 3)) & 3; }
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   f32x2 v = {lo, hi};
@@ -55,6 +60,15 @@ __device__ __forceinline__ float sumsq8(bf16x8 v, float acc) {
   acc = __builtin_amdgcn_fdot2_f32_bf16(p2, p2, acc, false);
   acc = __builtin_amdgcn_fdot2_f32_bf16(p3, p3, acc, false);
   return acc;
+}
+
+// 16 bytes per lane straight from global memory into LDS (no registers): the wave's 64
+// lanes fill 1 KiB starting at the wave-uniform LDS address `lds_wave_base`, lane i at
+// byte 16*i.  Completion is tracked by vmcnt.
+__device__ __forceinline__ void load_to_lds_16(const void* gptr, unsigned char* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds(
+      (const __attribute__((address_space(1))) void*)gptr,
+      (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
 }
 
 // Tile scheduling.  Workgroup ids are handed to the 8 XCDs round-robin and every XCD has
@@ -80,38 +94,62 @@ __global__ __launch_bounds__(kThreads) void restore_kernel(const RestoreArgs a, 
   if (tile_f >= g.nf || tile_t >= g.nt) return;
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave & 1, wn = wave >> 1;               // wave position: features / tokens
   const int l32 = lane & 31, lh = lane >> 5;
   const int d = a.d_model;
 
-  // ---- global -> LDS copy assignment: thread owns chunk lc of rows lr, lr+32, ...
-  const int lr = tid >> 3, lc = tid & 7;
-  const uint16_t* wsrc = a.wpack + (size_t)(tile_f * kTileF + lr) * d + lc * 8;
-  const uint16_t* xsrc[8];
+  // ---- global -> LDS assignment.  One wave instruction fills 16 rows x 64 bytes; wave w
+  // issues instructions q = 0..3 for rows (4w + q) * 16 .. + 15 of each operand.  Lane i
+  // writes chunk position i & 3 of row i >> 2, so it fetches logical chunk (i & 3) ^ f(row).
+  // Addresses are a wave-uniform base (advanced by 64 bytes per step with scalar adds) plus a
+  // per-lane 32-bit offset that never changes.
+  const unsigned char* wbase =
+      reinterpret_cast<const unsigned char*>(a.wpack) + (size_t)tile_f * kTileF * d * 2;
+  const unsigned char* xbase =
+      reinterpret_cast<const unsigned char*>(a.hidden) + (size_t)tile_t * kTileT * d * 2;
+  uint32_t woff[4], xoff[4];
 #pragma unroll
-  for (int p = 0; p < 8; ++p) {
-    int row = tile_t * kTileT + p * 32 + lr;
-    row = row < a.n_tok ? row : a.n_tok - 1;             // ragged tail: re-read the last row
-    xsrc[p] = a.hidden + (size_t)row * d + lc * 8;
+  for (int q = 0; q < 4; ++q) {
+    const int row = (wave * 4 + q) * 16 + (lane >> 2);
+    const int chunk = (lane & 3) ^ swizzle_of_row(row);
+    woff[q] = ((uint32_t)row * d + chunk * 8) * 2;
+    const int last = a.n_tok - 1 - tile_t * kTileT;      // ragged tail: re-read the last row
+    xoff[q] = ((uint32_t)(row < last ? row : last) * d + chunk * 8) * 2;
   }
-  int st_off[8];                                          // LDS byte offset inside an operand
-#pragma unroll
-  for (int p = 0; p < 8; ++p) {
-    const int row = p * 32 + lr;
-    st_off[p] = row * kRowBytes + ((lc ^ swizzle_of_row(row)) << 4);
-  }
+  const int nk = d / kTileK;
+  // One direct load (n = 0..7) of tile kt: even n -> weight rows, odd n -> token rows.
+  // Tiles past the end re-read the last one: the load count per step stays uniform and
+  // the data is never consumed.
+  auto issue_load = [&](int kt, int n) {
+    const int kk = kt < nk ? kt : nk - 1;
+    unsigned char* stage = lds + (kt & (kStages - 1)) * kStageBytes + wave * 4096;
+    const size_t koff = (size_t)kk * (kTileK * 2);
+    const int q = n >> 1;
+    if (n & 1) load_to_lds_16(xbase + koff + xoff[q], stage + kOperandBytes + q * 1024);
+    else       load_to_lds_16(wbase + koff + woff[q], stage + q * 1024);
+  };
 
-  // ---- LDS -> fragment read offsets (bytes inside an operand), per block and k sub-step
-  // fragment: lane reads 8 consecutive channels (one 16-byte chunk) of row l32 of its block;
-  // lanes 32..63 take the next chunk.
-  int a_row_off[4], b_row_off[4], a_sw[4], b_sw[4];
+  // ---- LDS -> fragment read offsets.  A fragment is 8 consecutive channels (one 16-byte
+  // chunk) of row l32 of a 32-row block; lanes 32..63 take the next chunk.  f(row) is the
+  // same for the four blocks of a wave (block stride 32 rows).
+  const int fl = swizzle_of_row(l32);
+  int a_off[2], b_off[2];                                // per k sub-step
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int ra = wm * 128 + i * 32 + l32, rb = wn * 128 + i * 32 + l32;
-    a_row_off[i] = ra * kRowBytes; a_sw[i] = swizzle_of_row(ra);
-    b_row_off[i] = rb * kRowBytes; b_sw[i] = swizzle_of_row(rb);
+  for (int ks = 0; ks < 2; ++ks) {
+    const int pc = ((ks * 2 + lh) ^ fl) << 4;
+    a_off[ks] = (wm * 128 + l32) * kRowBytes + pc;
+    b_off[ks] = kOperandBytes + (wn * 128 + l32) * kRowBytes + pc;
   }
+  // Fragment n = 0..7 of (tile kt, sub-step ks), in the order the matrix ops consume them:
+  // A0 B0 B1 B2 B3 A1 A2 A3.
+  auto read_frag = [&](int kt, int ks, int n, bf16x8 (&af)[4], bf16x8 (&bf)[4]) {
+    const unsigned char* stage = lds + (kt & (kStages - 1)) * kStageBytes;
+    if (n == 0)      af[0] = *reinterpret_cast<const bf16x8*>(stage + a_off[ks]);
+    else if (n <= 4) bf[n - 1] = *reinterpret_cast<const bf16x8*>(stage + b_off[ks] + (n - 1) * 32 * kRowBytes);
+    else             af[n - 4] = *reinterpret_cast<const bf16x8*>(stage + a_off[ks] + (n - 4) * 32 * kRowBytes);
+  };
 
   f32x16 acc[4][4];
 #pragma unroll
@@ -122,61 +160,51 @@ __global__ __launch_bounds__(kThreads) void restore_kernel(const RestoreArgs a, 
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
   float ss[4] = {0.f, 0.f, 0.f, 0.f};
 
-  u32x4 wreg[8], xreg[8];
-  const int nk = d / kTileK;
-
-  // prologue: stage 0
+  // ---- pipeline.  Stage kt % 4 holds tile kt.  Per step one barrier, placed after the
+  // fragments of the tile's second half are in registers: past it, the tile's stage is
+  // free (refilled with tile kt + 4) and tile kt + 1 is visible to every wave.
+  // The issue order is written out by hand and pinned with scheduling fences: every
+  // matrix op is followed by at most one LDS read or one global->LDS load plus the
+  // sum-of-squares dot products, so the matrix pipe never waits for the other ports.
+  bf16x8 af0[4], bf0[4], af1[4], bf1[4];
 #pragma unroll
-  for (int p = 0; p < 8; ++p) {
-    wreg[p] = *reinterpret_cast<const u32x4*>(wsrc + (size_t)p * 32 * d);
-    xreg[p] = *reinterpret_cast<const u32x4*>(xsrc[p]);
-  }
+  for (int s = 0; s < kStages; ++s)
 #pragma unroll
-  for (int p = 0; p < 8; ++p) {
-    *reinterpret_cast<u32x4*>(lds + st_off[p]) = wreg[p];
-    *reinterpret_cast<u32x4*>(lds + kOperandBytes + st_off[p]) = xreg[p];
-  }
-  __syncthreads();
+    for (int n = 0; n < 8; ++n) issue_load(s, n);
+  asm volatile("s_waitcnt vmcnt(24)" ::: "memory");      // tile 0 landed (3 x 8 loads may be in flight)
+  __builtin_amdgcn_s_barrier();
+#pragma unroll
+  for (int n = 0; n < 8; ++n) read_frag(0, 0, n, af0, bf0);
 
   for (int kt = 0; kt < nk; ++kt) {
-    const unsigned char* cur = lds + (kt & 1) * kStageBytes;
-    unsigned char* nxt = lds + ((kt + 1) & 1) * kStageBytes;
-    const bool more = kt + 1 < nk;
-    if (more) {
-      const int koff = (kt + 1) * kTileK;
+    // phase A: matrix ops on the first half (fragments already in registers) while the
+    // second half's fragments stream in from LDS
 #pragma unroll
-      for (int p = 0; p < 8; ++p) {
-        wreg[p] = *reinterpret_cast<const u32x4*>(wsrc + (size_t)p * 32 * d + koff);
-        xreg[p] = *reinterpret_cast<const u32x4*>(xsrc[p] + koff);
-      }
+    for (int n = 0; n < 16; ++n) {
+      const int i = n >> 2, j = n & 3;
+      if (n < 8) read_frag(kt, 1, n, af1, bf1);
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af0[i], bf0[j], acc[i][j], 0, 0, 0);
+      if (n < 4) ss[n] = sumsq8(bf0[n], ss[n]);
+      __builtin_amdgcn_sched_barrier(0);
     }
+    // tiles kt+2, kt+3 may still be in flight (2 x 8 loads); tile kt+1 must have landed
+    asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    // phase B: matrix ops on the second half while the first fragments of tile kt + 1
+    // stream in and the stage just consumed is refilled with tile kt + 4
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 af[4], bf[4];
-      const int chunk = ks * 2 + lh;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        af[i] = *reinterpret_cast<const bf16x8*>(cur + a_row_off[i] + ((chunk ^ a_sw[i]) << 4));
-        bf[i] = *reinterpret_cast<const bf16x8*>(cur + kOperandBytes + b_row_off[i] +
-                                                 ((chunk ^ b_sw[i]) << 4));
-      }
-#pragma unroll
-      for (int j = 0; j < 4; ++j) ss[j] = sumsq8(bf[j], ss[j]);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+    for (int n = 0; n < 16; ++n) {
+      const int i = n >> 2, j = n & 3;
+      if (n < 8) read_frag(kt + 1, 0, n, af0, bf0);
+      else       issue_load(kt + kStages, n - 8);
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af1[i], bf1[j], acc[i][j], 0, 0, 0);
+      if (n < 4) ss[n] = sumsq8(bf1[n], ss[n]);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    if (more) {
-#pragma unroll
-      for (int p = 0; p < 8; ++p) {
-        *reinterpret_cast<u32x4*>(nxt + st_off[p]) = wreg[p];
-        *reinterpret_cast<u32x4*>(nxt + kOperandBytes + st_off[p]) = xreg[p];
-      }
-    }
-    __syncthreads();
   }
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");   // drain the look-ahead loads
+  __syncthreads();
 
   // ---- epilogue: everything per token is per lane
   const int wave_f0 = tile_f * kTileF + wm * 128;         // first physical weight row of the wave
