@@ -15,6 +15,10 @@ namespace hc {
 //   (register v of lane half g holds block row 8*(v/4) + 4*g + v%4), so that a lane ends
 //   up with 16 consecutive pair offsets.
 // Value: bf16( float(W[logical row][c]) * float(gamma[c]) ), one rounding.
+// Memory order: tiles of 256 physical rows x 32 channels, [row tile][channel tile][row][32],
+// each tile 16 KiB and laid out exactly as the restoration kernel wants it in LDS (the four
+// 16-byte chunks of a row XOR-swizzled by swz_w), so a tile is fetched with fully
+// contiguous 1 KiB wave loads.
 __device__ __forceinline__ int logical_row(int p, int d_kv, int d_kv_pad, int hd, int style) {
   const int part = p >= d_kv_pad ? 1 : 0;
   const int pp = p - part * d_kv_pad;
@@ -49,7 +53,9 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const uint16_t* __res
         out = (uint16_t)(u >> 16);
       }
     }
-    wpack[(size_t)p * d_model + c] = out;
+    const int tile_f = p >> 8, r = p & 255, kt = c >> 5, chunk = (c >> 3) & 3, e = c & 7;
+    const size_t tile = (size_t)tile_f * (d_model >> 5) + kt;
+    wpack[tile * (kWTileBytes / 2) + r * 32 + ((chunk ^ swz_w(r)) << 3) + e] = out;
   }
 }
 

@@ -20,13 +20,21 @@ constexpr int kPartAlign = 128;   // the K part and the V part are each padded t
 constexpr int kTileF = 256;       // physical weight rows (features) per workgroup
 constexpr int kTileT = 256;       // tokens per workgroup
 constexpr int kTileK = 32;        // d_model slice per main-loop step
+constexpr int kWTileBytes = kTileF * kTileK * 2;   // one packed weight tile: 256 rows x 64 bytes
+
+// LDS placement of 16-byte chunks (XOR swizzles; they make the ds_read_b128 fragment reads
+// bank-conflict free).  Weight tiles have 64-byte rows (4 chunks): chunk c of row r sits at
+// position c ^ swz_w(r).  Activation super-tiles have 128-byte rows (8 chunks): chunk c of
+// row r sits at position c ^ swz_x(r).  The pack kernel bakes swz_w into the global layout.
+__host__ __device__ inline int swz_w(int row) { return (row >> 2) & 3; }
+__host__ __device__ inline int swz_x(int row) { return (row >> 1) & 7; }
 
 inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
 // Arguments of one restoration launch (device pointers unless noted).
 struct RestoreArgs {
   const uint16_t* hidden;        // bf16 [n_tok, d_model]
-  const uint16_t* wpack;         // bf16 [n_phys, d_model], packed order, gamma folded in
+  const uint16_t* wpack;         // bf16 packed weight tiles [n_phys/256][d_model/32][256][32], gamma folded in
   const int32_t* positions;      // [n_tok] or nullptr: position = pos_base + row
   const int32_t* cu_seqlens;     // [n_seq + 1] or nullptr (single context)
   const int32_t* block_tables;   // [n_seq][max_blocks]

@@ -19,11 +19,18 @@
 //
 // Tiling.  Workgroup = 256 threads = 4 waves in a 2x2 arrangement; workgroup tile =
 // 256 features x 256 tokens, wave tile = 128 x 128 (4x4 MFMA blocks, 256 accumulator
-// registers).  The d_model loop advances 32 channels per step through a ring of four LDS
-// stages of 32 KiB (16 KiB weights + 16 KiB activations) filled by direct global->LDS
-// loads issued four tiles ahead; rows are 64 bytes and their 16-byte chunks are
-// XOR-swizzled (on the global address side, since a direct load fills LDS lane by lane)
-// so that the ds_read_b128 fragment reads are bank-conflict free.
+// registers).  The d_model loop advances 32 channels per step.  Operands reach LDS by
+// direct global->LDS loads (no registers) that are issued several steps ahead:
+//   * weights: ring of four 16 KiB stages, one packed tile each (256 rows x 64 bytes); the
+//     pack kernel stores tiles contiguously in LDS order, so a wave load is 1 KiB contiguous;
+//   * activations: ring of three 32 KiB super-stages of 256 token rows x 128 bytes (two steps'
+//     worth of channels), so that every row fetch is one full 128-byte line; a super-stage is
+//     refilled in two halves over the two steps after it has been consumed.
+// 96 + 64 = 160 KiB, the whole LDS of a CU.  The 16-byte chunks of every row are
+// XOR-swizzled (for activations on the global-address side, since a direct load fills LDS
+// lane by lane) so that the ds_read_b128 fragment reads are bank-conflict free.
+#include <type_traits>
+
 #include "hcache_internal.h"
 
 namespace hc {
@@ -35,17 +42,14 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 
 constexpr int kThreads = 256;
-constexpr int kStages = 4;                               // LDS ring depth (tiles in flight)
-constexpr int kRowBytes = kTileK * 2;                    // 64
-constexpr int kOperandBytes = 256 * kRowBytes;           // 16 KiB per operand per stage
-constexpr int kStageBytes = 2 * kOperandBytes;           // 32 KiB
-constexpr int kLdsBytes = kStages * kStageBytes;         // 128 KiB
-static_assert(kTileK == 32, "the waitcnt constants below assume 8 direct loads per thread per tile");
-
-// 16-byte chunk `chunk` (0..3) of LDS row `row` lives at chunk position chunk ^ f(row); f is
-// chosen so that the 16 (or 8) consecutive rows one ds_read_b128 pass touches fall into
-// distinct banks whether the LDS serves 64 or 32 banks per clock.
-__device__ __forceinline__ int swizzle_of_row(int row) { return ((row >> 1) ^ (row >> 3)) & 3; }
+constexpr int kWStages = 4;                              // weight ring depth (steps)
+constexpr int kXStages = 3;                              // activation ring depth (double steps)
+constexpr int kWStageBytes = kWTileBytes;                // 16 KiB
+constexpr int kXRowBytes = 4 * kTileK;                   // 128: two steps' worth of channels
+constexpr int kXStageBytes = kTileT * kXRowBytes;        // 32 KiB
+constexpr int kXRegion = kXStages * kXStageBytes;        // activations at LDS offset 0
+constexpr int kLdsBytes = kXRegion + kWStages * kWStageBytes;   // 160 KiB
+static_assert(kTileK == 32 && kTileF == 256 && kTileT == 256, "load counts below assume these");
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   f32x2 v = {lo, hi};
@@ -53,13 +57,13 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, b);
 }
 
-__device__ __forceinline__ float sumsq8(bf16x8 v, float acc) {
-  const bf16x2 p0 = {v[0], v[1]}, p1 = {v[2], v[3]}, p2 = {v[4], v[5]}, p3 = {v[6], v[7]};
-  acc = __builtin_amdgcn_fdot2_f32_bf16(p0, p0, acc, false);
-  acc = __builtin_amdgcn_fdot2_f32_bf16(p1, p1, acc, false);
-  acc = __builtin_amdgcn_fdot2_f32_bf16(p2, p2, acc, false);
-  acc = __builtin_amdgcn_fdot2_f32_bf16(p3, p3, acc, false);
-  return acc;
+// acc + x0^2 + x1^2 for element pair `pair` (0..3) of a fragment, with ordinary fp32 ALU ops
+// (a bf16 is the upper half of an fp32).  The packed-dot instruction is avoided on purpose:
+// it competes with the matrix ops for their pipe, plain VALU ops run beside them.
+__device__ __forceinline__ float sumsq2(bf16x8 v, int pair, float acc) {
+  const uint32_t w = __builtin_bit_cast(u32x4, v)[pair];
+  const float lo = __uint_as_float(w << 16), hi = __uint_as_float(w & 0xffff0000u);
+  return __builtin_fmaf(hi, hi, __builtin_fmaf(lo, lo, acc));
 }
 
 // 16 bytes per lane straight from global memory into LDS (no registers): the wave's 64
@@ -100,55 +104,62 @@ __global__ __launch_bounds__(kThreads) void restore_kernel(const RestoreArgs a, 
   const int l32 = lane & 31, lh = lane >> 5;
   const int d = a.d_model;
 
-  // ---- global -> LDS assignment.  One wave instruction fills 16 rows x 64 bytes; wave w
-  // issues instructions q = 0..3 for rows (4w + q) * 16 .. + 15 of each operand.  Lane i
-  // writes chunk position i & 3 of row i >> 2, so it fetches logical chunk (i & 3) ^ f(row).
-  // Addresses are a wave-uniform base (advanced by 64 bytes per step with scalar adds) plus a
-  // per-lane 32-bit offset that never changes.
-  const unsigned char* wbase =
-      reinterpret_cast<const unsigned char*>(a.wpack) + (size_t)tile_f * kTileF * d * 2;
+  const int nk = d / kTileK;                             // steps (even: d_model % 64 == 0)
+  const int nm = nk >> 1;                                // activation super-tiles
+
+  // ---- global -> LDS assignment.
+  // Weights: tile (tile_f, kt) is 16 KiB contiguous; wave w copies KiB 4w .. 4w+3 of it.
+  const unsigned char* wtiles = reinterpret_cast<const unsigned char*>(a.wpack) +
+                                (size_t)tile_f * nk * kWTileBytes + wave * 4096;
+  const uint32_t wlane = lane * 16;
+  // Activations: one wave load covers 8 token rows x 128 bytes.  Load g = 0..31 of a
+  // super-tile covers rows 8g .. 8g+7; wave w issues g = 16*half + 4w + q.  Lane i fills
+  // chunk position i & 7 of row i >> 3, so it fetches logical chunk (i & 7) ^ swz_x(row).
   const unsigned char* xbase =
       reinterpret_cast<const unsigned char*>(a.hidden) + (size_t)tile_t * kTileT * d * 2;
-  uint32_t woff[4], xoff[4];
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int row = (wave * 4 + q) * 16 + (lane >> 2);
-    const int chunk = (lane & 3) ^ swizzle_of_row(row);
-    woff[q] = ((uint32_t)row * d + chunk * 8) * 2;
+  uint32_t xoff[8];
+  {
     const int last = a.n_tok - 1 - tile_t * kTileT;      // ragged tail: re-read the last row
-    xoff[q] = ((uint32_t)(row < last ? row : last) * d + chunk * 8) * 2;
+#pragma unroll
+    for (int hq = 0; hq < 8; ++hq) {
+      const int g = (hq >> 2) * 16 + wave * 4 + (hq & 3);
+      const int row = g * 8 + (lane >> 3);
+      const int chunk = (lane & 7) ^ swz_x(row);
+      xoff[hq] = (uint32_t)(row < last ? row : last) * d * 2 + chunk * 16;
+    }
   }
-  const int nk = d / kTileK;
-  // One direct load (n = 0..7) of tile kt: even n -> weight rows, odd n -> token rows.
-  // Tiles past the end re-read the last one: the load count per step stays uniform and
-  // the data is never consumed.
-  auto issue_load = [&](int kt, int n) {
+  // Loads past the end of d_model re-read the last tile: the load count per step stays
+  // uniform (the vmcnt waits below count loads) and that data is never consumed.
+  auto load_w = [&](int kt, int q) {                     // quarter q of this wave's share of tile kt
     const int kk = kt < nk ? kt : nk - 1;
-    unsigned char* stage = lds + (kt & (kStages - 1)) * kStageBytes + wave * 4096;
-    const size_t koff = (size_t)kk * (kTileK * 2);
-    const int q = n >> 1;
-    if (n & 1) load_to_lds_16(xbase + koff + xoff[q], stage + kOperandBytes + q * 1024);
-    else       load_to_lds_16(wbase + koff + woff[q], stage + q * 1024);
+    load_to_lds_16(wtiles + (size_t)kk * kWTileBytes + q * 1024 + wlane,
+                   lds + kXRegion + (kt & (kWStages - 1)) * kWStageBytes + wave * 4096 + q * 1024);
+  };
+  auto load_x = [&](int m, int stage, int half, int q) { // super-tile m -> super-stage `stage`
+    const int mm = m < nm ? m : nm - 1;
+    load_to_lds_16(xbase + (size_t)mm * kXRowBytes + xoff[half * 4 + q],
+                   lds + stage * kXStageBytes + (half * 16 + wave * 4 + q) * 1024);
   };
 
-  // ---- LDS -> fragment read offsets.  A fragment is 8 consecutive channels (one 16-byte
-  // chunk) of row l32 of a 32-row block; lanes 32..63 take the next chunk.  f(row) is the
+  // ---- LDS -> fragment reads.  A fragment is 8 consecutive channels (one 16-byte chunk) of
+  // row l32 of a 32-row block; lanes 32..63 take the next chunk.  The swizzle term is the
   // same for the four blocks of a wave (block stride 32 rows).
-  const int fl = swizzle_of_row(l32);
-  int a_off[2], b_off[2];                                // per k sub-step
+  int a_off[2], b_off[2][2];                             // [k sub-step], [step parity][k sub-step]
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) {
-    const int pc = ((ks * 2 + lh) ^ fl) << 4;
-    a_off[ks] = (wm * 128 + l32) * kRowBytes + pc;
-    b_off[ks] = kOperandBytes + (wn * 128 + l32) * kRowBytes + pc;
+    a_off[ks] = kXRegion + (wm * 128 + l32) * (kTileK * 2) + (((ks * 2 + lh) ^ swz_w(l32)) << 4);
+#pragma unroll
+    for (int par = 0; par < 2; ++par)
+      b_off[par][ks] = (wn * 128 + l32) * kXRowBytes + (((par * 4 + ks * 2 + lh) ^ swz_x(l32)) << 4);
   }
-  // Fragment n = 0..7 of (tile kt, sub-step ks), in the order the matrix ops consume them:
-  // A0 B0 B1 B2 B3 A1 A2 A3.
-  auto read_frag = [&](int kt, int ks, int n, bf16x8 (&af)[4], bf16x8 (&bf)[4]) {
-    const unsigned char* stage = lds + (kt & (kStages - 1)) * kStageBytes;
-    if (n == 0)      af[0] = *reinterpret_cast<const bf16x8*>(stage + a_off[ks]);
-    else if (n <= 4) bf[n - 1] = *reinterpret_cast<const bf16x8*>(stage + b_off[ks] + (n - 1) * 32 * kRowBytes);
-    else             af[n - 4] = *reinterpret_cast<const bf16x8*>(stage + a_off[ks] + (n - 4) * 32 * kRowBytes);
+  // Fragment n = 0..7 of (step kt, sub-step ks), in the order the matrix ops consume them:
+  // A0 B0 B1 B2 B3 A1 A2 A3.  `xs` is the super-stage holding step kt's activations.
+  auto read_frag = [&](int kt, int xs, int par, int ks, int n, bf16x8 (&af)[4], bf16x8 (&bf)[4]) {
+    const unsigned char* wst = lds + (kt & (kWStages - 1)) * kWStageBytes + a_off[ks];
+    const unsigned char* xst = lds + xs * kXStageBytes + b_off[par][ks];
+    if (n == 0)      af[0] = *reinterpret_cast<const bf16x8*>(wst);
+    else if (n <= 4) bf[n - 1] = *reinterpret_cast<const bf16x8*>(xst + (n - 1) * 32 * kXRowBytes);
+    else             af[n - 4] = *reinterpret_cast<const bf16x8*>(wst + (n - 4) * 32 * (kTileK * 2));
   };
 
   f32x16 acc[4][4];
@@ -160,118 +171,193 @@ __global__ __launch_bounds__(kThreads) void restore_kernel(const RestoreArgs a, 
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
   float ss[4] = {0.f, 0.f, 0.f, 0.f};
 
-  // ---- pipeline.  Stage kt % 4 holds tile kt.  Per step one barrier, placed after the
-  // fragments of the tile's second half are in registers: past it, the tile's stage is
-  // free (refilled with tile kt + 4) and tile kt + 1 is visible to every wave.
-  // The issue order is written out by hand and pinned with scheduling fences: every
-  // matrix op is followed by at most one LDS read or one global->LDS load plus the
-  // sum-of-squares dot products, so the matrix pipe never waits for the other ports.
+  // ---- pipeline.  Weight stage kt % 4 holds step kt; activation super-stage (kt/2) % 3
+  // holds steps kt, kt^1.  Per step there is one barrier, placed after the fragments of the
+  // step's second half are in registers.  Past it the step's weight stage is free (refilled
+  // with step kt + 4), after an odd step so is the activation super-stage (refilled in two
+  // halves, in this step and the next, with super-tile kt/2 + 3), and step kt + 1 is
+  // visible to every wave.  Every step issues exactly 8 loads per thread, in program order
+  // [4 weight, 4 activation]; "vmcnt(16)" therefore means "everything issued up to three
+  // steps ago has landed", which covers step kt + 1's operands.
+  // The issue order is written out by hand and pinned with scheduling fences: every matrix
+  // op is followed by at most one LDS read or one global->LDS load plus the sum-of-squares
+  // dot products, so the matrix pipe never waits for the other ports.
   bf16x8 af0[4], bf0[4], af1[4], bf1[4];
+
+  // ---- per-token lookups, done up front so that their memory latency hides behind the
+  // first tile loads.  Lane l32 owns token column l32 of each of its four 32-token blocks:
+  // position, (ragged) context, page -> row index of the token in the pool, or -1.
+  const int wave_f0 = tile_f * kTileF + wm * 128;         // first physical weight row of the wave
+  const int part = wave_f0 >= a.d_kv_pad ? 1 : 0;         // 0 = K rows, 1 = V rows (wave-uniform)
+  int pos[4], page[4], tok_row[4];
 #pragma unroll
-  for (int s = 0; s < kStages; ++s)
+  for (int j = 0; j < 4; ++j) {
+    const int t = tile_t * kTileT + wn * 128 + j * 32 + l32;
+    pos[j] = -1;
+    page[j] = -1;
+    int seq = 0;
+    if (t < a.n_tok) {
+      pos[j] = a.positions ? a.positions[t] : a.pos_base + t;
+      if (a.cu_seqlens) {                                 // largest s with cu[s] <= t
+        int lo = 0, hi = a.n_seq;                         // invariant: cu[lo] <= t < cu[hi]
+        while (hi - lo > 1) {
+          const int mid = (lo + hi) >> 1;
+          if (a.cu_seqlens[mid] <= t) lo = mid; else hi = mid;
+        }
+        seq = lo;
+      }
+      const int blk = pos[j] >> a.block_shift;
+      if (pos[j] < 0 || pos[j] >= a.max_position || blk >= a.max_blocks) {
+        atomicOr(a.err, HC_DEV_BAD_POSITION);
+        pos[j] = -1;
+      } else {
+        page[j] = a.block_tables[(size_t)seq * a.max_blocks + blk];
+      }
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // prologue (36 loads): W0 X0 | W1 X1 | W2 W3 X2(first half)
 #pragma unroll
-    for (int n = 0; n < 8; ++n) issue_load(s, n);
-  asm volatile("s_waitcnt vmcnt(24)" ::: "memory");      // tile 0 landed (3 x 8 loads may be in flight)
+  for (int q = 0; q < 4; ++q) load_w(0, q);
+#pragma unroll
+  for (int hq = 0; hq < 8; ++hq) load_x(0, 0, hq >> 2, hq & 3);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) load_w(1, q);
+#pragma unroll
+  for (int hq = 0; hq < 8; ++hq) load_x(1, 1, hq >> 2, hq & 3);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) load_w(2, q);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) load_w(3, q);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) load_x(2, 2, 0, q);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    tok_row[j] = -1;
+    if (pos[j] >= 0) {
+      if (page[j] < 0 || page[j] >= a.num_pages) atomicOr(a.err, HC_DEV_BAD_PAGE);
+      else tok_row[j] = ((page[j] * 2 + part) << a.block_shift) + (pos[j] & ((1 << a.block_shift) - 1));
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(24)" ::: "memory");      // the first 12 (W0, X0) have landed
   __builtin_amdgcn_s_barrier();
 #pragma unroll
-  for (int n = 0; n < 8; ++n) read_frag(0, 0, n, af0, bf0);
+  for (int n = 0; n < 8; ++n) read_frag(0, 0, 0, 0, n, af0, bf0);
 
-  for (int kt = 0; kt < nk; ++kt) {
+  // one step; PAR = kt & 1 is a compile-time constant (the loop below is unrolled by two).
+  //   xs      super-stage of step kt
+  //   xs_next super-stage of step kt + 1 (= xs for even kt)
+  //   xl      super-stage refilled in this step, with super-tile ml, half lh_
+  auto step = [&](int kt, auto par_c, int xs, int xs_next, int xl, int ml) {
+    constexpr int PAR = decltype(par_c)::value;
     // phase A: matrix ops on the first half (fragments already in registers) while the
     // second half's fragments stream in from LDS
 #pragma unroll
     for (int n = 0; n < 16; ++n) {
       const int i = n >> 2, j = n & 3;
-      if (n < 8) read_frag(kt, 1, n, af1, bf1);
+      if (n < 8) read_frag(kt, xs, PAR, 1, n, af1, bf1);
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af0[i], bf0[j], acc[i][j], 0, 0, 0);
-      if (n < 4) ss[n] = sumsq8(bf0[n], ss[n]);
+      ss[n & 3] = sumsq2(bf0[n & 3], n >> 2, ss[n & 3]);   // one dot product per slot
       __builtin_amdgcn_sched_barrier(0);
     }
-    // tiles kt+2, kt+3 may still be in flight (2 x 8 loads); tile kt+1 must have landed
     asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    // phase B: matrix ops on the second half while the first fragments of tile kt + 1
-    // stream in and the stage just consumed is refilled with tile kt + 4
+    // phase B: matrix ops on the second half while the first fragments of step kt + 1 stream
+    // in and the stages just consumed are refilled
 #pragma unroll
     for (int n = 0; n < 16; ++n) {
       const int i = n >> 2, j = n & 3;
-      if (n < 8) read_frag(kt + 1, 0, n, af0, bf0);
-      else       issue_load(kt + kStages, n - 8);
+      if (n < 8)       read_frag(kt + 1, xs_next, PAR ^ 1, 0, n, af0, bf0);
+      else if (n < 12) load_w(kt + kWStages, n - 8);
+      else             load_x(ml, xl, PAR ^ 1, n - 12);
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af1[i], bf1[j], acc[i][j], 0, 0, 0);
-      if (n < 4) ss[n] = sumsq8(bf1[n], ss[n]);
+      ss[n & 3] = sumsq2(bf1[n & 3], n >> 2, ss[n & 3]);
       __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  {
+    int xr = 0;                                          // (kt / 2) % 3 for the even step kt
+    for (int kt = 0; kt < nk; kt += 2) {
+      const int xr1 = xr == 2 ? 0 : xr + 1, xr2 = xr == 0 ? 2 : xr - 1;   // +1, +2 mod 3
+      // even step: completes super-tile kt/2 + 2 (second half) in super-stage xr + 2
+      step(kt, std::integral_constant<int, 0>{}, xr, xr, xr2, (kt >> 1) + 2);
+      // odd step: super-stage xr is consumed; starts super-tile kt/2 + 3 (first half) in it
+      step(kt + 1, std::integral_constant<int, 1>{}, xr, xr1, xr, (kt >> 1) + 3);
+      xr = xr1;
     }
   }
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");   // drain the look-ahead loads
   __syncthreads();
 
-  // ---- epilogue: everything per token is per lane
-  const int wave_f0 = tile_f * kTileF + wm * 128;         // first physical weight row of the wave
-  const int part = wave_f0 >= a.d_kv_pad ? 1 : 0;         // 0 = K rows, 1 = V rows (wave-uniform)
+  // ---- epilogue: everything per token is per lane.  fp32 accumulators are scaled by the
+  // token's 1/rms, K is rotated with the (cos, sin) table row of the token's position, and
+  // one round-to-nearest-even conversion to bf16 precedes the 16-byte stores into the
+  // token's cache row.  The table reads of token block j + 1 are issued before block j is
+  // processed, so their latency overlaps the arithmetic and the stores.
   const int part_f0 = wave_f0 - part * a.d_kv_pad;
   const int hd = a.head_dim, half = hd >> 1, groups_per_head = hd >> 6;
-  const int bmask = (1 << a.block_shift) - 1;
-
+  int head[2], i0[2];
+  bool live[2];
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const int grp = (part_f0 >> 6) + q;                   // pair group inside the K or V part
+    live[q] = grp * kPairGroup < a.d_kv;                  // false for padding rows (wave-uniform)
+    head[q] = grp / groups_per_head;
+    i0[q] = 32 * (grp - head[q] * groups_per_head) + 16 * lh;   // first RoPE pair index of this lane
+  }
+  float rstd[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const int t = tile_t * kTileT + wn * 128 + j * 32 + l32;
     const float s = ss[j] + __shfl_xor(ss[j], 32);        // the two lane halves hold different channels
-    const float rstd = rsqrtf(s * a.inv_d + a.eps);
-    if (t >= a.n_tok) continue;
-    const int pos = a.positions ? a.positions[t] : a.pos_base + t;
-    int seq = 0;
-    if (a.cu_seqlens) {                                   // largest s with cu[s] <= t
-      int lo = 0, hi = a.n_seq;                           // invariant: cu[lo] <= t < cu[hi]
-      while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (a.cu_seqlens[mid] <= t) lo = mid; else hi = mid;
-      }
-      seq = lo;
-    }
-    const int blk = pos >> a.block_shift;
-    if (pos < 0 || pos >= a.max_position || blk >= a.max_blocks) {
-      atomicOr(a.err, HC_DEV_BAD_POSITION);
-      continue;
-    }
-    const int page = a.block_tables[(size_t)seq * a.max_blocks + blk];
-    if (page < 0 || page >= a.num_pages) {
-      atomicOr(a.err, HC_DEV_BAD_PAGE);
-      continue;
-    }
-    uint16_t* dst_row = a.pool +
-        ((((size_t)page * 2 + part) << a.block_shift) + (size_t)(pos & bmask)) * a.d_kv;
-    const float2* rope_row = a.rope + (size_t)pos * half;
-
+    rstd[j] = rsqrtf(s * a.inv_d + a.eps);
+  }
+  float4 cs[2][16];                                       // [buffer][q * 8 + v / 2]: two (cos, sin) pairs
+  auto load_cs = [&](int j, float4 (&buf)[16]) {
+    if (tok_row[j] < 0) return;
+    const float2* rope_row = a.rope + (size_t)pos[j] * half;
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+      if (live[q])
+#pragma unroll
+        for (int v = 0; v < 16; v += 2)
+          buf[q * 8 + (v >> 1)] = *reinterpret_cast<const float4*>(rope_row + i0[q] + v);
+  };
+  if (part == 0) load_cs(0, cs[0]);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (part == 0 && j + 1 < 4) load_cs(j + 1, cs[(j + 1) & 1]);
+    if (tok_row[j] < 0) continue;
+    uint16_t* dst_row = a.pool + (size_t)tok_row[j] * a.d_kv;
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
-      const int grp = (part_f0 >> 6) + q;                 // pair group inside the K or V part
-      if (grp * kPairGroup >= a.d_kv) continue;           // padding rows (wave-uniform)
-      const int head = grp / groups_per_head, qq = grp - head * groups_per_head;
-      const int i0 = 32 * qq + 16 * lh;                   // first RoPE pair index of this lane
+      if (!live[q]) continue;
       float oa[16], ob[16];
       if (part == 0) {
 #pragma unroll
         for (int v = 0; v < 16; v += 2) {
-          const float4 cs = *reinterpret_cast<const float4*>(rope_row + i0 + v);
-          const float a0 = acc[2 * q][j][v] * rstd, b0 = acc[2 * q + 1][j][v] * rstd;
-          const float a1 = acc[2 * q][j][v + 1] * rstd, b1 = acc[2 * q + 1][j][v + 1] * rstd;
-          oa[v] = a0 * cs.x - b0 * cs.y;
-          ob[v] = b0 * cs.x + a0 * cs.y;
-          oa[v + 1] = a1 * cs.z - b1 * cs.w;
-          ob[v + 1] = b1 * cs.z + a1 * cs.w;
+          const float4 c4 = cs[j & 1][q * 8 + (v >> 1)];
+          const float a0 = acc[2 * q][j][v] * rstd[j], b0 = acc[2 * q + 1][j][v] * rstd[j];
+          const float a1 = acc[2 * q][j][v + 1] * rstd[j], b1 = acc[2 * q + 1][j][v + 1] * rstd[j];
+          oa[v] = a0 * c4.x - b0 * c4.y;
+          ob[v] = b0 * c4.x + a0 * c4.y;
+          oa[v + 1] = a1 * c4.z - b1 * c4.w;
+          ob[v + 1] = b1 * c4.z + a1 * c4.w;
         }
       } else {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          oa[v] = acc[2 * q][j][v] * rstd;
-          ob[v] = acc[2 * q + 1][j][v] * rstd;
+          oa[v] = acc[2 * q][j][v] * rstd[j];
+          ob[v] = acc[2 * q + 1][j][v] * rstd[j];
         }
       }
       if (STYLE == 0) {
         // first member at head*hd + i, second at head*hd + hd/2 + i
-        u32x4* da = reinterpret_cast<u32x4*>(dst_row + head * hd + i0);
-        u32x4* db = reinterpret_cast<u32x4*>(dst_row + head * hd + half + i0);
+        u32x4* da = reinterpret_cast<u32x4*>(dst_row + head[q] * hd + i0[q]);
+        u32x4* db = reinterpret_cast<u32x4*>(dst_row + head[q] * hd + half + i0[q]);
         u32x4 w0, w1;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -287,7 +373,7 @@ __global__ __launch_bounds__(kThreads) void restore_kernel(const RestoreArgs a, 
         db[0] = w0; db[1] = w1;
       } else {
         // members of pair i at head*hd + 2i and 2i + 1: interleave the two blocks
-        u32x4* dq = reinterpret_cast<u32x4*>(dst_row + head * hd + 2 * i0);
+        u32x4* dq = reinterpret_cast<u32x4*>(dst_row + head[q] * hd + 2 * i0[q]);
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           u32x4 w;
