@@ -17,9 +17,12 @@
 // makes those 16 features consecutive in the cache row and puts the two members of
 // every RoPE pair into the same lane and register index of two neighbouring blocks.
 //
-// Tiling.  Workgroup = 256 threads = 4 waves in a 2x2 arrangement; workgroup tile =
-// 256 features x 256 tokens, wave tile = 128 x 128 (4x4 MFMA blocks, 256 accumulator
-// registers).  The d_model loop advances 32 channels per step.  Operands reach LDS by
+// Tiling.  Workgroup = 512 threads = 8 waves, two per SIMD, arranged 2 (features) x 4
+// (tokens); workgroup tile = 256 features x 256 tokens, wave tile = 128 x 64 (4x2 MFMA
+// blocks, 128 accumulator registers).  Two waves share a SIMD on purpose: a wave cannot
+// issue anything else while one of its matrix ops occupies the pipe, so the LDS reads,
+// global loads and vector ALU work of one wave run in the shadow of the other wave's
+// matrix ops.  The d_model loop advances 32 channels per step.  Operands reach LDS by
 // direct global->LDS loads (no registers) that are issued several steps ahead:
 //   * weights: ring of four 16 KiB stages, one packed tile each (256 rows x 64 bytes); the
 //     pack kernel stores tiles contiguously in LDS order, so a wave load is 1 KiB contiguous;
@@ -41,7 +44,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 512;
 constexpr int kWStages = 4;                              // weight ring depth (steps)
 constexpr int kXStages = 3;                              // activation ring depth (double steps)
 constexpr int kWStageBytes = kWTileBytes;                // 16 KiB
@@ -100,7 +103,7 @@ __global__ __launch_bounds__(kThreads) void restore_kernel(const RestoreArgs a, 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave & 1, wn = wave >> 1;               // wave position: features / tokens
+  const int wm = wave & 1, wn = wave >> 1;               // wave position: features (2) / tokens (4)
   const int l32 = lane & 31, lh = lane >> 5;
   const int d = a.d_model;
 
@@ -108,21 +111,21 @@ __global__ __launch_bounds__(kThreads) void restore_kernel(const RestoreArgs a, 
   const int nm = nk >> 1;                                // activation super-tiles
 
   // ---- global -> LDS assignment.
-  // Weights: tile (tile_f, kt) is 16 KiB contiguous; wave w copies KiB 4w .. 4w+3 of it.
+  // Weights: tile (tile_f, kt) is 16 KiB contiguous; wave w copies KiB 2w, 2w+1 of it.
   const unsigned char* wtiles = reinterpret_cast<const unsigned char*>(a.wpack) +
-                                (size_t)tile_f * nk * kWTileBytes + wave * 4096;
+                                (size_t)tile_f * nk * kWTileBytes + wave * 2048;
   const uint32_t wlane = lane * 16;
   // Activations: one wave load covers 8 token rows x 128 bytes.  Load g = 0..31 of a
-  // super-tile covers rows 8g .. 8g+7; wave w issues g = 16*half + 4w + q.  Lane i fills
+  // super-tile covers rows 8g .. 8g+7; wave w issues g = 16*half + 2w + q.  Lane i fills
   // chunk position i & 7 of row i >> 3, so it fetches logical chunk (i & 7) ^ swz_x(row).
   const unsigned char* xbase =
       reinterpret_cast<const unsigned char*>(a.hidden) + (size_t)tile_t * kTileT * d * 2;
-  uint32_t xoff[8];
+  uint32_t xoff[4];
   {
     const int last = a.n_tok - 1 - tile_t * kTileT;      // ragged tail: re-read the last row
 #pragma unroll
-    for (int hq = 0; hq < 8; ++hq) {
-      const int g = (hq >> 2) * 16 + wave * 4 + (hq & 3);
+    for (int hq = 0; hq < 4; ++hq) {
+      const int g = (hq >> 1) * 16 + wave * 2 + (hq & 1);
       const int row = g * 8 + (lane >> 3);
       const int chunk = (lane & 7) ^ swz_x(row);
       xoff[hq] = (uint32_t)(row < last ? row : last) * d * 2 + chunk * 16;
@@ -130,69 +133,60 @@ __global__ __launch_bounds__(kThreads) void restore_kernel(const RestoreArgs a, 
   }
   // Loads past the end of d_model re-read the last tile: the load count per step stays
   // uniform (the vmcnt waits below count loads) and that data is never consumed.
-  auto load_w = [&](int kt, int q) {                     // quarter q of this wave's share of tile kt
+  auto load_w = [&](int kt, int q) {                     // half q of this wave's share of tile kt
     const int kk = kt < nk ? kt : nk - 1;
     load_to_lds_16(wtiles + (size_t)kk * kWTileBytes + q * 1024 + wlane,
-                   lds + kXRegion + (kt & (kWStages - 1)) * kWStageBytes + wave * 4096 + q * 1024);
+                   lds + kXRegion + (kt & (kWStages - 1)) * kWStageBytes + wave * 2048 + q * 1024);
   };
   auto load_x = [&](int m, int stage, int half, int q) { // super-tile m -> super-stage `stage`
     const int mm = m < nm ? m : nm - 1;
-    load_to_lds_16(xbase + (size_t)mm * kXRowBytes + xoff[half * 4 + q],
-                   lds + stage * kXStageBytes + (half * 16 + wave * 4 + q) * 1024);
+    load_to_lds_16(xbase + (size_t)mm * kXRowBytes + xoff[half * 2 + q],
+                   lds + stage * kXStageBytes + (half * 16 + wave * 2 + q) * 1024);
   };
 
   // ---- LDS -> fragment reads.  A fragment is 8 consecutive channels (one 16-byte chunk) of
   // row l32 of a 32-row block; lanes 32..63 take the next chunk.  The swizzle term is the
-  // same for the four blocks of a wave (block stride 32 rows).
+  // same for all blocks of a wave (block stride 32 rows).
   int a_off[2], b_off[2][2];                             // [k sub-step], [step parity][k sub-step]
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) {
     a_off[ks] = kXRegion + (wm * 128 + l32) * (kTileK * 2) + (((ks * 2 + lh) ^ swz_w(l32)) << 4);
 #pragma unroll
     for (int par = 0; par < 2; ++par)
-      b_off[par][ks] = (wn * 128 + l32) * kXRowBytes + (((par * 4 + ks * 2 + lh) ^ swz_x(l32)) << 4);
+      b_off[par][ks] = (wn * 64 + l32) * kXRowBytes + (((par * 4 + ks * 2 + lh) ^ swz_x(l32)) << 4);
   }
-  // Fragment n = 0..7 of (step kt, sub-step ks), in the order the matrix ops consume them:
-  // A0 B0 B1 B2 B3 A1 A2 A3.  `xs` is the super-stage holding step kt's activations.
-  auto read_frag = [&](int kt, int xs, int par, int ks, int n, bf16x8 (&af)[4], bf16x8 (&bf)[4]) {
+  // Fragment n = 0..5 of (step kt, sub-step ks), in the order the matrix ops consume them:
+  // A0 B0 B1 A1 A2 A3.  `xs` is the super-stage holding step kt's activations.
+  auto read_frag = [&](int kt, int xs, int par, int ks, int n, bf16x8 (&af)[4], bf16x8 (&bf)[2]) {
     const unsigned char* wst = lds + (kt & (kWStages - 1)) * kWStageBytes + a_off[ks];
     const unsigned char* xst = lds + xs * kXStageBytes + b_off[par][ks];
     if (n == 0)      af[0] = *reinterpret_cast<const bf16x8*>(wst);
-    else if (n <= 4) bf[n - 1] = *reinterpret_cast<const bf16x8*>(xst + (n - 1) * 32 * kXRowBytes);
-    else             af[n - 4] = *reinterpret_cast<const bf16x8*>(wst + (n - 4) * 32 * (kTileK * 2));
+    else if (n <= 2) bf[n - 1] = *reinterpret_cast<const bf16x8*>(xst + (n - 1) * 32 * kXRowBytes);
+    else             af[n - 2] = *reinterpret_cast<const bf16x8*>(wst + (n - 2) * 32 * (kTileK * 2));
   };
 
-  f32x16 acc[4][4];
+  f32x16 acc[4][2];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-  float ss[4] = {0.f, 0.f, 0.f, 0.f};
+  // sum of squares of the token column this wave is responsible for: the two waves that
+  // share a token range (wm = 0, 1) split its two 32-token blocks between them
+  float ssum = 0.f;
 
-  // ---- pipeline.  Weight stage kt % 4 holds step kt; activation super-stage (kt/2) % 3
-  // holds steps kt, kt^1.  Per step there is one barrier, placed after the fragments of the
-  // step's second half are in registers.  Past it the step's weight stage is free (refilled
-  // with step kt + 4), after an odd step so is the activation super-stage (refilled in two
-  // halves, in this step and the next, with super-tile kt/2 + 3), and step kt + 1 is
-  // visible to every wave.  Every step issues exactly 8 loads per thread, in program order
-  // [4 weight, 4 activation]; "vmcnt(16)" therefore means "everything issued up to three
-  // steps ago has landed", which covers step kt + 1's operands.
-  // The issue order is written out by hand and pinned with scheduling fences: every matrix
-  // op is followed by at most one LDS read or one global->LDS load plus the sum-of-squares
-  // dot products, so the matrix pipe never waits for the other ports.
-  bf16x8 af0[4], bf0[4], af1[4], bf1[4];
+  bf16x8 af0[4], bf0[2], af1[4], bf1[2];
 
   // ---- per-token lookups, done up front so that their memory latency hides behind the
-  // first tile loads.  Lane l32 owns token column l32 of each of its four 32-token blocks:
+  // first tile loads.  Lane l32 owns token column l32 of each of its two 32-token blocks:
   // position, (ragged) context, page -> row index of the token in the pool, or -1.
   const int wave_f0 = tile_f * kTileF + wm * 128;         // first physical weight row of the wave
   const int part = wave_f0 >= a.d_kv_pad ? 1 : 0;         // 0 = K rows, 1 = V rows (wave-uniform)
-  int pos[4], page[4], tok_row[4];
+  int pos[2], page[2], tok_row[2];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int t = tile_t * kTileT + wn * 128 + j * 32 + l32;
+  for (int j = 0; j < 2; ++j) {
+    const int t = tile_t * kTileT + wn * 64 + j * 32 + l32;
     pos[j] = -1;
     page[j] = -1;
     int seq = 0;
@@ -216,80 +210,95 @@ __global__ __launch_bounds__(kThreads) void restore_kernel(const RestoreArgs a, 
     }
   }
   __builtin_amdgcn_sched_barrier(0);
-  // prologue (36 loads): W0 X0 | W1 X1 | W2 W3 X2(first half)
+  // prologue (18 loads per thread): W0 X0 | W1 X1 | W2 W3 X2(first half)
 #pragma unroll
-  for (int q = 0; q < 4; ++q) load_w(0, q);
+  for (int q = 0; q < 2; ++q) load_w(0, q);
 #pragma unroll
-  for (int hq = 0; hq < 8; ++hq) load_x(0, 0, hq >> 2, hq & 3);
+  for (int hq = 0; hq < 4; ++hq) load_x(0, 0, hq >> 1, hq & 1);
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-  for (int q = 0; q < 4; ++q) load_w(1, q);
+  for (int q = 0; q < 2; ++q) load_w(1, q);
 #pragma unroll
-  for (int hq = 0; hq < 8; ++hq) load_x(1, 1, hq >> 2, hq & 3);
+  for (int hq = 0; hq < 4; ++hq) load_x(1, 1, hq >> 1, hq & 1);
 #pragma unroll
-  for (int q = 0; q < 4; ++q) load_w(2, q);
+  for (int q = 0; q < 2; ++q) load_w(2, q);
 #pragma unroll
-  for (int q = 0; q < 4; ++q) load_w(3, q);
+  for (int q = 0; q < 2; ++q) load_w(3, q);
 #pragma unroll
-  for (int q = 0; q < 4; ++q) load_x(2, 2, 0, q);
+  for (int q = 0; q < 2; ++q) load_x(2, 2, 0, q);
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < 2; ++j) {
     tok_row[j] = -1;
     if (pos[j] >= 0) {
       if (page[j] < 0 || page[j] >= a.num_pages) atomicOr(a.err, HC_DEV_BAD_PAGE);
       else tok_row[j] = ((page[j] * 2 + part) << a.block_shift) + (pos[j] & ((1 << a.block_shift) - 1));
     }
   }
-  asm volatile("s_waitcnt vmcnt(24)" ::: "memory");      // the first 12 (W0, X0) have landed
+  asm volatile("s_waitcnt vmcnt(12)" ::: "memory");      // the first 6 (W0, X0) have landed
   __builtin_amdgcn_s_barrier();
 #pragma unroll
-  for (int n = 0; n < 8; ++n) read_frag(0, 0, 0, 0, n, af0, bf0);
+  for (int n = 0; n < 6; ++n) read_frag(0, 0, 0, 0, n, af0, bf0);
 
-  // one step; PAR = kt & 1 is a compile-time constant (the loop below is unrolled by two).
+  // ---- pipeline.  Weight stage kt % 4 holds step kt; activation super-stage (kt/2) % 3
+  // holds steps kt, kt^1.  Per step there is one barrier, placed after the fragments of the
+  // step's second half are in registers.  Past it the step's weight stage is free (refilled
+  // with step kt + 4), after an odd step so is the activation super-stage (refilled in two
+  // halves, in this step and the next, with super-tile kt/2 + 3), and step kt + 1 is
+  // visible to every wave.  Every step issues exactly 4 loads per thread, in program order
+  // [2 weight, 2 activation]; "vmcnt(8)" therefore means "everything issued up to three
+  // steps ago has landed", which covers step kt + 1's operands.
+  // The issue order is written out by hand and pinned with scheduling fences: every matrix
+  // op is followed by at most one LDS read or one global->LDS load plus a few ALU ops.
+  //
+  // one step; PAR = kt & 1 and WM = wm are compile-time constants.
   //   xs      super-stage of step kt
   //   xs_next super-stage of step kt + 1 (= xs for even kt)
-  //   xl      super-stage refilled in this step, with super-tile ml, half lh_
-  auto step = [&](int kt, auto par_c, int xs, int xs_next, int xl, int ml) {
+  //   xl      super-stage refilled in this step, with super-tile ml
+  auto step = [&](int kt, auto par_c, auto wm_c, int xs, int xs_next, int xl, int ml) {
     constexpr int PAR = decltype(par_c)::value;
+    constexpr int WM = decltype(wm_c)::value;
     // phase A: matrix ops on the first half (fragments already in registers) while the
     // second half's fragments stream in from LDS
 #pragma unroll
-    for (int n = 0; n < 16; ++n) {
-      const int i = n >> 2, j = n & 3;
-      if (n < 8) read_frag(kt, xs, PAR, 1, n, af1, bf1);
+    for (int n = 0; n < 8; ++n) {
+      const int i = n >> 1, j = n & 1;
+      if (n < 6) read_frag(kt, xs, PAR, 1, n, af1, bf1);
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af0[i], bf0[j], acc[i][j], 0, 0, 0);
-      ss[n & 3] = sumsq2(bf0[n & 3], n >> 2, ss[n & 3]);   // one dot product per slot
+      if (n < 4) ssum = sumsq2(bf0[WM], n, ssum);
       __builtin_amdgcn_sched_barrier(0);
     }
-    asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
+    asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     // phase B: matrix ops on the second half while the first fragments of step kt + 1 stream
     // in and the stages just consumed are refilled
 #pragma unroll
-    for (int n = 0; n < 16; ++n) {
-      const int i = n >> 2, j = n & 3;
-      if (n < 8)       read_frag(kt + 1, xs_next, PAR ^ 1, 0, n, af0, bf0);
-      else if (n < 12) load_w(kt + kWStages, n - 8);
-      else             load_x(ml, xl, PAR ^ 1, n - 12);
+    for (int n = 0; n < 8; ++n) {
+      const int i = n >> 1, j = n & 1;
+      if (n < 6) read_frag(kt + 1, xs_next, PAR ^ 1, 0, n, af0, bf0);
+      if (n >= 4) {
+        if (n < 6) load_w(kt + kWStages, n - 4);
+        else       load_x(ml, xl, PAR ^ 1, n - 6);
+      }
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af1[i], bf1[j], acc[i][j], 0, 0, 0);
-      ss[n & 3] = sumsq2(bf1[n & 3], n >> 2, ss[n & 3]);
+      if (n < 4) ssum = sumsq2(bf1[WM], n, ssum);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-
-  {
+  auto run = [&](auto wm_c) {
     int xr = 0;                                          // (kt / 2) % 3 for the even step kt
     for (int kt = 0; kt < nk; kt += 2) {
       const int xr1 = xr == 2 ? 0 : xr + 1, xr2 = xr == 0 ? 2 : xr - 1;   // +1, +2 mod 3
       // even step: completes super-tile kt/2 + 2 (second half) in super-stage xr + 2
-      step(kt, std::integral_constant<int, 0>{}, xr, xr, xr2, (kt >> 1) + 2);
+      step(kt, std::integral_constant<int, 0>{}, wm_c, xr, xr, xr2, (kt >> 1) + 2);
       // odd step: super-stage xr is consumed; starts super-tile kt/2 + 3 (first half) in it
-      step(kt + 1, std::integral_constant<int, 1>{}, xr, xr1, xr, (kt >> 1) + 3);
+      step(kt + 1, std::integral_constant<int, 1>{}, wm_c, xr, xr1, xr, (kt >> 1) + 3);
       xr = xr1;
     }
-  }
+  };
+  if (wm == 0) run(std::integral_constant<int, 0>{});
+  else         run(std::integral_constant<int, 1>{});
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");   // drain the look-ahead loads
   __syncthreads();
 
@@ -298,6 +307,16 @@ __global__ __launch_bounds__(kThreads) void restore_kernel(const RestoreArgs a, 
   // one round-to-nearest-even conversion to bf16 precedes the 16-byte stores into the
   // token's cache row.  The table reads of token block j + 1 are issued before block j is
   // processed, so their latency overlaps the arithmetic and the stores.
+  float rstd[2];
+  {
+    // exchange the sums of squares between the two waves of a token range through LDS
+    float* sums = reinterpret_cast<float*>(lds);          // [wn][block][32]
+    const float s = ssum + __shfl_xor(ssum, 32);          // the two lane halves hold different channels
+    if (lh == 0) sums[(wn * 2 + wm) * 32 + l32] = s;
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 2; ++j) rstd[j] = rsqrtf(sums[(wn * 2 + j) * 32 + l32] * a.inv_d + a.eps);
+  }
   const int part_f0 = wave_f0 - part * a.d_kv_pad;
   const int hd = a.head_dim, half = hd >> 1, groups_per_head = hd >> 6;
   int head[2], i0[2];
@@ -309,79 +328,58 @@ __global__ __launch_bounds__(kThreads) void restore_kernel(const RestoreArgs a, 
     head[q] = grp / groups_per_head;
     i0[q] = 32 * (grp - head[q] * groups_per_head) + 16 * lh;   // first RoPE pair index of this lane
   }
-  float rstd[4];
+  // batches b = 2 j + q: token block j, pair group q
+  float4 cs[2][8];                                        // [buffer][v / 2]: two (cos, sin) pairs each
+  auto load_cs = [&](int b, float4 (&buf)[8]) {
+    const int j = b >> 1, q = b & 1;
+    if (part != 0 || tok_row[j] < 0 || !live[q]) return;
+    const float2* rope_row = a.rope + (size_t)pos[j] * half + i0[q];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const float s = ss[j] + __shfl_xor(ss[j], 32);        // the two lane halves hold different channels
-    rstd[j] = rsqrtf(s * a.inv_d + a.eps);
-  }
-  float4 cs[2][16];                                       // [buffer][q * 8 + v / 2]: two (cos, sin) pairs
-  auto load_cs = [&](int j, float4 (&buf)[16]) {
-    if (tok_row[j] < 0) return;
-    const float2* rope_row = a.rope + (size_t)pos[j] * half;
-#pragma unroll
-    for (int q = 0; q < 2; ++q)
-      if (live[q])
-#pragma unroll
-        for (int v = 0; v < 16; v += 2)
-          buf[q * 8 + (v >> 1)] = *reinterpret_cast<const float4*>(rope_row + i0[q] + v);
+    for (int v = 0; v < 16; v += 2) buf[v >> 1] = *reinterpret_cast<const float4*>(rope_row + v);
   };
-  if (part == 0) load_cs(0, cs[0]);
+  load_cs(0, cs[0]);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    if (part == 0 && j + 1 < 4) load_cs(j + 1, cs[(j + 1) & 1]);
-    if (tok_row[j] < 0) continue;
-    uint16_t* dst_row = a.pool + (size_t)tok_row[j] * a.d_kv;
+  for (int b = 0; b < 4; ++b) {
+    const int j = b >> 1, q = b & 1;
+    if (b + 1 < 4) load_cs(b + 1, cs[(b + 1) & 1]);
+    if (tok_row[j] < 0 || !live[q]) continue;
+    uint16_t* dst = a.pool + (size_t)tok_row[j] * a.d_kv + head[q] * hd;
+    uint32_t pa[8], pb[8];                                // bf16 pairs of the first / second members
+    if (part == 0) {
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      if (!live[q]) continue;
-      float oa[16], ob[16];
-      if (part == 0) {
-#pragma unroll
-        for (int v = 0; v < 16; v += 2) {
-          const float4 c4 = cs[j & 1][q * 8 + (v >> 1)];
-          const float a0 = acc[2 * q][j][v] * rstd[j], b0 = acc[2 * q + 1][j][v] * rstd[j];
-          const float a1 = acc[2 * q][j][v + 1] * rstd[j], b1 = acc[2 * q + 1][j][v + 1] * rstd[j];
-          oa[v] = a0 * c4.x - b0 * c4.y;
-          ob[v] = b0 * c4.x + a0 * c4.y;
-          oa[v + 1] = a1 * c4.z - b1 * c4.w;
-          ob[v + 1] = b1 * c4.z + a1 * c4.w;
-        }
-      } else {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          oa[v] = acc[2 * q][j][v] * rstd[j];
-          ob[v] = acc[2 * q + 1][j][v] * rstd[j];
-        }
+      for (int v = 0; v < 16; v += 2) {
+        const float4 c4 = cs[b & 1][v >> 1];
+        const float a0 = acc[2 * q][j][v] * rstd[j], b0 = acc[2 * q + 1][j][v] * rstd[j];
+        const float a1 = acc[2 * q][j][v + 1] * rstd[j], b1 = acc[2 * q + 1][j][v + 1] * rstd[j];
+        const float ra0 = a0 * c4.x - b0 * c4.y, rb0 = b0 * c4.x + a0 * c4.y;
+        const float ra1 = a1 * c4.z - b1 * c4.w, rb1 = b1 * c4.z + a1 * c4.w;
+        if (STYLE == 0) { pa[v >> 1] = pack_bf16x2(ra0, ra1); pb[v >> 1] = pack_bf16x2(rb0, rb1); }
+        else            { pa[v >> 1] = pack_bf16x2(ra0, rb0); pb[v >> 1] = pack_bf16x2(ra1, rb1); }
       }
-      if (STYLE == 0) {
-        // first member at head*hd + i, second at head*hd + hd/2 + i
-        u32x4* da = reinterpret_cast<u32x4*>(dst_row + head[q] * hd + i0[q]);
-        u32x4* db = reinterpret_cast<u32x4*>(dst_row + head[q] * hd + half + i0[q]);
-        u32x4 w0, w1;
+    } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          w0[e] = pack_bf16x2(oa[2 * e], oa[2 * e + 1]);
-          w1[e] = pack_bf16x2(oa[8 + 2 * e], oa[8 + 2 * e + 1]);
-        }
-        da[0] = w0; da[1] = w1;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          w0[e] = pack_bf16x2(ob[2 * e], ob[2 * e + 1]);
-          w1[e] = pack_bf16x2(ob[8 + 2 * e], ob[8 + 2 * e + 1]);
-        }
-        db[0] = w0; db[1] = w1;
-      } else {
-        // members of pair i at head*hd + 2i and 2i + 1: interleave the two blocks
-        u32x4* dq = reinterpret_cast<u32x4*>(dst_row + head[q] * hd + 2 * i0[q]);
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          u32x4 w;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) w[e] = pack_bf16x2(oa[4 * c + e], ob[4 * c + e]);
-          dq[c] = w;
-        }
+      for (int v = 0; v < 16; v += 2) {
+        const float a0 = acc[2 * q][j][v] * rstd[j], b0 = acc[2 * q + 1][j][v] * rstd[j];
+        const float a1 = acc[2 * q][j][v + 1] * rstd[j], b1 = acc[2 * q + 1][j][v + 1] * rstd[j];
+        if (STYLE == 0) { pa[v >> 1] = pack_bf16x2(a0, a1); pb[v >> 1] = pack_bf16x2(b0, b1); }
+        else            { pa[v >> 1] = pack_bf16x2(a0, b0); pb[v >> 1] = pack_bf16x2(a1, b1); }
       }
+    }
+    if (STYLE == 0) {
+      // first members at head*hd + i, second members at head*hd + hd/2 + i
+      u32x4* da = reinterpret_cast<u32x4*>(dst + i0[q]);
+      u32x4* db = reinterpret_cast<u32x4*>(dst + half + i0[q]);
+      da[0] = u32x4{pa[0], pa[1], pa[2], pa[3]};
+      da[1] = u32x4{pa[4], pa[5], pa[6], pa[7]};
+      db[0] = u32x4{pb[0], pb[1], pb[2], pb[3]};
+      db[1] = u32x4{pb[4], pb[5], pb[6], pb[7]};
+    } else {
+      // members of pair i at head*hd + 2i and 2i + 1: pa/pb hold (first, second) of even/odd v
+      u32x4* dq = reinterpret_cast<u32x4*>(dst + 2 * i0[q]);
+      dq[0] = u32x4{pa[0], pb[0], pa[1], pb[1]};
+      dq[1] = u32x4{pa[2], pb[2], pa[3], pb[3]};
+      dq[2] = u32x4{pa[4], pb[4], pa[5], pb[5]};
+      dq[3] = u32x4{pa[6], pb[6], pa[7], pb[7]};
     }
   }
 }
