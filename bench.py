@@ -67,6 +67,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-e2e", action="store_true")
     ap.add_argument("--e2e-steps", type=int, default=5)
+    ap.add_argument("--loader", type=int, default=0, help="0 = copy engines, strided runs (default), 1 = gather kernel")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB -> 256 MiB streaming kernel three times, so that a "
                          "counter run has a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
@@ -171,6 +172,7 @@ def main():
                 rows = hidden_host[l][c * CT:(c + 1) * CT]
                 store.append(0, l, rows, len(rows))
         copy_stream = torch.cuda.Stream()
+        ctx.set_loader(args.loader)
         for _ in range(2):
             ctx.restore_context(store, 0, 0, T, w.pos_offset, d_bt, len(bt), stream,
                                 copy_stream.cuda_stream)
@@ -196,7 +198,8 @@ def main():
         e2e = {"ms_per_restore": round(e2e_ms, 3), "tokens_per_s": round(T / (e2e_ms * 1e-3), 1),
                "host_link_GBps": round(host_bytes / (e2e_ms * 1e-3) / 1e9, 2),
                "plain_pinned_h2d_GBps": round(h2d_gbs, 2), "chunk_tokens": CT,
-               "note": "chunk store -> hipMemcpyAsync on a side stream -> kernel, layer pipelined"}
+               "loader": "copy engines, strided runs" if args.loader == 0 else "gather kernel",
+               "note": "pinned chunk store -> loader on a side stream -> kernel, layer pipelined"}
         assert ctx.poll_device_error(stream) == 0
         store.destroy()
 

@@ -174,15 +174,25 @@ hc_status hc_store_drop(hc_store* store, int64_t seq_id);
 /* Restore ALL layers of tokens [tok_begin, tok_begin + n_tok) of one stored context,
  * token i sitting at absolute position pos_offset + i (Section 3.1 pipeline; Section 5
  * "Pipelined state transmission").  Per layer the chunks are copied to one of two HBM
- * staging buffers with hipMemcpyAsync on `copy_stream`, and the restoration kernel runs
- * on `compute_stream`; events order the two so that the transfer of layer L+1 overlaps
- * the kernel of layer L.  Staging buffers are allocated inside the call when the
+ * staging buffers on `copy_stream` -- by the copy engines, one (strided) hipMemcpy2DAsync /
+ * hipMemcpyAsync per run of equally spaced chunks, or by a gather kernel that reads the
+ * pinned arena over the host link (hc_set_loader) -- and the restoration kernel runs on
+ * `compute_stream`;
+ * events order the two so that the transfer of layer L+1 overlaps the kernel of layer L.  Staging buffers are allocated inside the call when the
  * context has none large enough.  Returns after everything is enqueued; the caller
  * synchronises `compute_stream`.  The two streams must differ. */
 hc_status hc_restore_context(hc_ctx* ctx, const hc_store* store, int64_t seq_id,
                              int32_t tok_begin, int32_t n_tok, int32_t pos_offset,
                              const int32_t* d_block_table, int32_t n_blocks,
                              void* compute_stream, void* copy_stream);
+
+/* Loader used by hc_restore_context: 0 (default) = copy engines: chunks of a layer whose
+ * arena slots are equally spaced (the usual result of saving in generation order) move in
+ * ONE strided copy, irregular placements in one copy per run; the compute units stay free
+ * for the restoration kernel.  1 = gather kernel reading the pinned arena directly, one
+ * launch per layer (pinned stores only; reaches the link rate for any placement, but its
+ * waves share compute units with the restoration kernel and slow it down). */
+hc_status hc_set_loader(hc_ctx* ctx, int32_t mode);
 
 /* ---- measurement hooks -------------------------------------------------------------
  * Average duration in milliseconds of the restoration kernel launches queued on

@@ -58,6 +58,7 @@ def _load():
         "hc_store_chunk": (i32, [vp, i64, i32, i32, p(vp), p(i32)]),
         "hc_store_drop": (i32, [vp, i64]),
         "hc_restore_context": (i32, [vp, vp, i64, i32, i32, i32, vp, i32, vp, vp]),
+        "hc_set_loader": (i32, [vp, i32]),
         "hc_timing_begin": (i32, [vp]),
         "hc_timing_end": (i32, [vp, vp, p(C.c_double), p(i32)]),
     }
@@ -71,7 +72,7 @@ lib = _load()
 EXPORTED = ("hc_last_error hc_version hc_validate_desc hc_create hc_destroy hc_set_layer_weights "
             "hc_set_kv_pool hc_restore_kv hc_restore_kv_ragged hc_poll_device_error hc_store_create "
             "hc_store_create_ex hc_store_destroy hc_store_append hc_store_tokens hc_store_chunk "
-            "hc_store_drop hc_restore_context hc_timing_begin hc_timing_end").split()
+            "hc_store_drop hc_restore_context hc_set_loader hc_timing_begin hc_timing_end").split()
 
 
 def _check(status):
@@ -143,6 +144,9 @@ class Context:
                         compute_stream, copy_stream):
         _check(lib.hc_restore_context(self._h, store._h, seq_id, tok_begin, n_tok, pos_offset,
                                       _ptr(d_block_table), n_blocks, compute_stream, copy_stream))
+
+    def set_loader(self, mode):
+        _check(lib.hc_set_loader(self._h, mode))
 
     def timing_begin(self):
         _check(lib.hc_timing_begin(self._h))

@@ -164,6 +164,10 @@ hc_status hc_destroy(hc_ctx* ctx) {
     if (ctx->h2d_done[i]) (void)hipEventDestroy(ctx->h2d_done[i]);
     if (ctx->buf_free[i]) (void)hipEventDestroy(ctx->buf_free[i]);
   }
+  for (int i = 0; i < 2; ++i) {
+    if (ctx->seg_tab[i]) (void)hipHostFree(ctx->seg_tab[i]);
+    if (ctx->seg_done[i]) (void)hipEventDestroy(ctx->seg_done[i]);
+  }
   for (hipEvent_t e : ctx->ev_pool) (void)hipEventDestroy(e);
   delete ctx;
   return HC_OK;
@@ -243,6 +247,14 @@ hc_status hc_poll_device_error(hc_ctx* ctx, void* stream, int32_t* out_flags) {
   HC_HIP(hipMemcpyAsync(out_flags, ctx->err_dev, sizeof(int32_t), hipMemcpyDeviceToHost, st));
   HC_HIP(hipMemsetAsync(ctx->err_dev, 0, sizeof(int32_t), st));
   HC_HIP(hipStreamSynchronize(st));
+  return HC_OK;
+}
+
+hc_status hc_set_loader(hc_ctx* ctx, int32_t mode) {
+  clear_error();
+  if (!ctx) return fail(HC_EINVAL, "ctx is null");
+  if (mode != 0 && mode != 1) return fail(HC_EINVAL, "loader mode must be 0 (copy engines) or 1 (gather kernel)");
+  ctx->loader_mode = mode;
   return HC_OK;
 }
 

@@ -96,4 +96,40 @@ hipError_t launch_rope_table(float2* table, int max_position, int head_dim, doub
   return hipGetLastError();
 }
 
+// ---- chunk gather ---------------------------------------------------------------------
+// Host->HBM loader of the pipelined restore (paper Section 5, "Pipelined state
+// transmission"): the chunks of one layer sit at arbitrary places of the pinned host arena.
+// A few workgroups read them over the host link with 16-byte loads (several in flight per
+// lane) and write the staging buffer; measured at the link's full rate, which a sequence of
+// per-chunk hipMemcpyAsync calls does not reach.  Each segment is served by
+// kGatherBlocksPerSegment workgroups, each taking an interleaved share of its 16-byte words.
+typedef __attribute__((ext_vector_type(4))) uint32_t gather_vec;
+
+__global__ __launch_bounds__(256) void gather_segments_kernel(const CopySegment* __restrict__ segs,
+                                                              int n_seg) {
+  const int seg = blockIdx.x / kGatherBlocksPerSegment;
+  const int share = blockIdx.x - seg * kGatherBlocksPerSegment;
+  if (seg >= n_seg) return;
+  const gather_vec* src = static_cast<const gather_vec*>(segs[seg].src);
+  gather_vec* dst = static_cast<gather_vec*>(segs[seg].dst);
+  const long n = (long)(segs[seg].bytes >> 4);
+  const long stride = (long)kGatherBlocksPerSegment * 256;
+  for (long i = (long)share * 256 + threadIdx.x; i < n; i += 4 * stride) {
+    gather_vec v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (i + u * stride < n) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (i + u * stride < n) dst[i + u * stride] = v[u];
+  }
+}
+
+hipError_t launch_gather(const CopySegment* segs, int n_seg, hipStream_t stream) {
+  if (n_seg <= 0) return hipSuccess;
+  hipLaunchKernelGGL(gather_segments_kernel, dim3(n_seg * kGatherBlocksPerSegment), dim3(256), 0,
+                     stream, segs, n_seg);
+  return hipGetLastError();
+}
+
 }  // namespace hc

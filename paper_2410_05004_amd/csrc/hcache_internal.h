@@ -66,6 +66,18 @@ hipError_t launch_rope_table(float2* table, int max_position, int head_dim, doub
                              hipStream_t stream);
 hipError_t configure_kernels();   // one-time function attributes (dynamic LDS size)
 
+// One contiguous piece of a layer's hidden states in the host store and where it goes in
+// the HBM staging buffer.  `bytes` is a multiple of 16.
+struct CopySegment {
+  const void* src;   // pinned host memory (device-readable)
+  void* dst;         // HBM
+  uint64_t bytes;
+};
+constexpr int kGatherBlocksPerSegment = 8;
+// Copies n_seg segments with a kernel that reads the pinned host memory directly
+// (kGatherBlocksPerSegment workgroups per segment); `segs` must be device-readable.
+hipError_t launch_gather(const CopySegment* segs, int n_seg, hipStream_t stream);
+
 // Error plumbing: thread-local message + status.
 hc_status fail(hc_status code, const std::string& msg);
 hc_status fail_hip(hipError_t e, const char* what);
@@ -108,6 +120,13 @@ struct hc_ctx {
   int64_t stage_tokens = 0;
   hipEvent_t h2d_done[2] = {nullptr, nullptr};
   hipEvent_t buf_free[2] = {nullptr, nullptr};
+  int loader_mode = 0;                    // 0 = copy engines (strided runs), 1 = gather kernel
+  // segment tables of the gather loader: pinned host memory the kernel reads directly; two of
+  // them, used alternately, each guarded by an event recorded after its last reader
+  hc::CopySegment* seg_tab[2] = {nullptr, nullptr};
+  size_t seg_cap[2] = {0, 0};
+  hipEvent_t seg_done[2] = {nullptr, nullptr};
+  int seg_next = 0;
   // per-launch timing
   bool timing = false;
   std::vector<hipEvent_t> ev_pool;        // created on demand, reused

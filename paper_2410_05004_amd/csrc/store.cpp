@@ -219,20 +219,101 @@ hc_status hc_restore_context(hc_ctx* ctx, const hc_store* st, int64_t seq_id, in
     }
   }
 
+  // Segments: one per run of equally spaced chunks of a layer.  Chunks that arrive in
+  // generation order are spaced n_layers slots apart (or adjacent after a long prefill), so a
+  // whole layer is usually a single run: one strided copy.
   const int CT = st->chunk_tokens;
   const int c_first = tok_begin / CT, c_last = (tok_begin + n_tok - 1) / CT;
-  for (int l = 0; l < L; ++l) {
-    const int b = l & 1;
-    // the kernel that last read stage[b] (two layers ago, or a previous call) must be done
-    HC_HIP(hipStreamWaitEvent(xs, ctx->buf_free[b], 0));
-    for (int c = c_first; c <= c_last; ++c) {
+  struct Run { const unsigned char* src; unsigned char* dst; size_t row_bytes; size_t pitch; int rows; };
+  std::vector<Run> runs;
+  std::vector<CopySegment> segs;                        // host scratch
+  auto stage_at = [&](int b, int c, int lo) {
+    return reinterpret_cast<unsigned char*>(ctx->stage[b]) + (size_t)(c * CT + lo - tok_begin) * st->row_bytes;
+  };
+  auto build = [&](int l, int b) {
+    runs.clear();
+    segs.clear();
+    for (int c = c_first; c <= c_last; ++c) {           // one segment per chunk (gather kernel)
       const int lo = c == c_first ? tok_begin - c * CT : 0;
       const int hi = c == c_last ? tok_begin + n_tok - c * CT : CT;
-      const unsigned char* src = st->arena + (size_t)s.chunks[l][c] * st->chunk_bytes +
-                                 (size_t)lo * st->row_bytes;
-      unsigned char* dst = reinterpret_cast<unsigned char*>(ctx->stage[b]) +
-                           (size_t)(c * CT + lo - tok_begin) * st->row_bytes;
-      HC_HIP(hipMemcpyAsync(dst, src, (size_t)(hi - lo) * st->row_bytes, hipMemcpyHostToDevice, xs));
+      CopySegment g;
+      g.src = st->arena + (size_t)s.chunks[l][c] * st->chunk_bytes + (size_t)lo * st->row_bytes;
+      g.dst = stage_at(b, c, lo);
+      g.bytes = (size_t)(hi - lo) * st->row_bytes;
+      segs.push_back(g);
+    }
+    // runs for the copy engines: partial first / last chunks on their own, full chunks grouped
+    // while their arena slots stay equally spaced
+    int c = c_first;
+    while (c <= c_last) {
+      const int lo = c == c_first ? tok_begin - c * CT : 0;
+      const int hi = c == c_last ? tok_begin + n_tok - c * CT : CT;
+      const unsigned char* src = st->arena + (size_t)s.chunks[l][c] * st->chunk_bytes + (size_t)lo * st->row_bytes;
+      if (lo != 0 || hi != CT) {
+        runs.push_back({src, stage_at(b, c, lo), (size_t)(hi - lo) * st->row_bytes, 0, 1});
+        ++c;
+        continue;
+      }
+      int c_end = c;
+      int64_t stride = 0;
+      auto full = [&](int cc) { return cc < c_last || tok_begin + n_tok - cc * CT == CT; };
+      if (c + 1 <= c_last && full(c + 1)) {
+        stride = s.chunks[l][c + 1] - s.chunks[l][c];
+        if (stride > 0) {
+          c_end = c + 1;
+          while (c_end + 1 <= c_last && full(c_end + 1) &&
+                 s.chunks[l][c_end + 1] - s.chunks[l][c_end] == stride) ++c_end;
+        }
+      }
+      runs.push_back({src, stage_at(b, c, 0), st->chunk_bytes, (size_t)stride * st->chunk_bytes, c_end - c + 1});
+      c = c_end + 1;
+    }
+  };
+
+  // The gather kernel needs a device-readable arena and reads its segment table from pinned
+  // host memory; a pageable arena goes through hipMemcpyAsync.
+  const bool use_gather = st->pinned && ctx->loader_mode == 1;
+  CopySegment* tab = nullptr;
+  size_t tab_used = 0;
+  int tab_id = 0;
+  if (use_gather) {
+    tab_id = ctx->seg_next;
+    ctx->seg_next ^= 1;
+    const size_t need = (size_t)L * (size_t)(c_last - c_first + 1);
+    if (!ctx->seg_done[tab_id]) HC_HIP(hipEventCreateWithFlags(&ctx->seg_done[tab_id], hipEventDisableTiming));
+    else HC_HIP(hipEventSynchronize(ctx->seg_done[tab_id]));   // kernels of an earlier call still reading it
+    if (ctx->seg_cap[tab_id] < need) {
+      if (ctx->seg_tab[tab_id]) { HC_HIP(hipHostFree(ctx->seg_tab[tab_id])); ctx->seg_tab[tab_id] = nullptr; }
+      ctx->seg_cap[tab_id] = 0;
+      void* p = nullptr;
+      hipError_t e = hipHostMalloc(&p, need * sizeof(CopySegment), hipHostMallocDefault);
+      if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(HC_ENOMEM, "pinned allocation of the segment table failed");
+      }
+      ctx->seg_tab[tab_id] = static_cast<CopySegment*>(p);
+      ctx->seg_cap[tab_id] = need;
+    }
+    tab = ctx->seg_tab[tab_id];
+  }
+
+  for (int l = 0; l < L; ++l) {
+    const int b = l & 1;
+    build(l, b);
+    // the kernel that last read stage[b] (two layers ago, or a previous call) must be done
+    HC_HIP(hipStreamWaitEvent(xs, ctx->buf_free[b], 0));
+    if (use_gather) {
+      memcpy(tab + tab_used, segs.data(), segs.size() * sizeof(CopySegment));
+      HC_HIP(launch_gather(tab + tab_used, (int)segs.size(), xs));
+      tab_used += segs.size();
+    } else {
+      for (const Run& r : runs) {
+        if (r.rows == 1 || r.pitch == r.row_bytes)
+          HC_HIP(hipMemcpyAsync(r.dst, r.src, r.row_bytes * r.rows, hipMemcpyHostToDevice, xs));
+        else
+          HC_HIP(hipMemcpy2DAsync(r.dst, r.row_bytes, r.src, r.pitch, r.row_bytes, r.rows,
+                                  hipMemcpyHostToDevice, xs));
+      }
     }
     HC_HIP(hipEventRecord(ctx->h2d_done[b], xs));
     HC_HIP(hipStreamWaitEvent(cs, ctx->h2d_done[b], 0));
@@ -241,6 +322,7 @@ hc_status hc_restore_context(hc_ctx* ctx, const hc_store* st, int64_t seq_id, in
     if (r != HC_OK) return r;
     HC_HIP(hipEventRecord(ctx->buf_free[b], cs));
   }
+  if (use_gather) HC_HIP(hipEventRecord(ctx->seg_done[tab_id], xs));
   return HC_OK;
 }
 

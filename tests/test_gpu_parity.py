@@ -213,16 +213,19 @@ def test_host_side_errors(hc, torch):
     ctx.destroy()
 
 
-def test_restore_context_from_store(hc, torch):
-    """Whole-context pipelined restore from the pinned chunk store: all layers, a token range
-    that starts and ends inside chunks, positions offset so the first page is part filled."""
+@pytest.mark.parametrize("pinned,loader", [(True, 0), (True, 1), (False, 0)],
+                         ids=["copy-engines", "gather-kernel", "pageable-store"])
+def test_restore_context_from_store(hc, torch, pinned, loader):
+    """Whole-context pipelined restore from the chunk store: all layers, a token range that
+    starts and ends inside chunks, positions offset so the first page is part filled; with
+    the gather-kernel loader, the hipMemcpyAsync loader, and a store in pageable memory."""
     rng = np.random.default_rng(31)
     L, d_model, n_kv, hd, B, CT = 5, 512, 2, 128, 16, 64
     T_stored, tok_begin, n_tok, pos_offset = 700, 30, 650, 1000
     desc = gh.make_desc(hc, n_layers=L, d_model=d_model, n_q_heads=n_kv, n_kv_heads=n_kv,
                         head_dim=hd, block_size=B, max_position=pos_offset + T_stored)
     cases = [gh.LayerCase(np.random.default_rng([31, l]), d_model, n_kv, hd, T_stored) for l in range(L)]
-    store = hc.Store(L, d_model, CT, capacity_chunks=L * ((T_stored + CT - 1) // CT) + 2, pinned=True)
+    store = hc.Store(L, d_model, CT, capacity_chunks=L * ((T_stored + CT - 1) // CT) + 2, pinned=pinned)
     # save order: a 512-token prefill, then smaller appends, layer by layer each time
     cuts = [0, 512, 600, 601, 700]
     for a, b in zip(cuts[:-1], cuts[1:]):
@@ -242,6 +245,7 @@ def test_restore_context_from_store(hc, torch):
         pools.append(gh.new_pool(num_pages, B, n_kv, hd))
         ctx.set_kv_pool(l, pools[l], num_pages)
     d_bt = gh.to_dev_i32(bt)
+    ctx.set_loader(loader)
     torch.cuda.synchronize()
     for rep in range(2):                                # second call reuses the staging buffers
         ctx.restore_context(store, 3, tok_begin, n_tok, pos_offset, d_bt, n_blocks, s,
