@@ -4,12 +4,15 @@
 namespace hc {
 
 // ---- weight packing -------------------------------------------------------------------
-// Physical row order of the packed weights [2 * d_kv_pad, d_model]:
-//   part   = K rows first (padded to a multiple of 128 rows with zeros), then V rows;
-//   inside a part, rows come in "pair groups" of 64: group G covers head G / (hd/64) and
-//   RoPE pair indices [32 qq, 32 qq + 32), qq = G % (hd/64).  The first 32 rows of a group
-//   are the first members of those pairs, the last 32 rows the second members
-//   (half-split: features i and i + hd/2; interleaved: features 2i and 2i + 1);
+// Physical row order of the packed weights [2 * d_kv_pad, d_model], d_kv_pad = d_kv rounded
+// up to 128:
+//   rows come in "pair groups" of 64; K groups and V groups alternate (K0 V0 K1 V1 ...), so
+//   that every 128-row wave tile carries one K group (which needs RoPE) and one V group
+//   (which does not) and all waves have the same amount of epilogue work.  Group g of a part
+//   covers head g / (hd/64) and RoPE pair indices [32 qq, 32 qq + 32), qq = g % (hd/64);
+//   groups at or beyond d_kv / 64 are zero padding.  The first 32 rows of a group are the
+//   first members of those pairs, the last 32 rows the second members (half-split: features
+//   i and i + hd/2; interleaved: features 2i and 2i + 1; V rows use the same order);
 //   inside a 32-row block, row i maps to pair offset u = 16*((i/4)%2) + 4*(i/8) + i%4,
 //   which is the order in which a lane of v_mfma_f32_32x32x16 receives its 16 outputs
 //   (register v of lane half g holds block row 8*(v/4) + 4*g + v%4), so that a lane ends
@@ -20,11 +23,10 @@ namespace hc {
 // 16-byte chunks of a row XOR-swizzled by swz_w), so a tile is fetched with fully
 // contiguous 1 KiB wave loads.
 __device__ __forceinline__ int logical_row(int p, int d_kv, int d_kv_pad, int hd, int style) {
-  const int part = p >= d_kv_pad ? 1 : 0;
-  const int pp = p - part * d_kv_pad;
-  const int grp = pp >> 6;
+  const int part = (p >> 6) & 1;                          // K and V groups alternate
+  const int grp = p >> 7;
   if (grp * kPairGroup >= d_kv) return -1;                // padding
-  const int member = (pp >> 5) & 1, i = pp & 31;
+  const int member = (p >> 5) & 1, i = p & 31;
   const int u = 16 * ((i >> 2) & 1) + 4 * (i >> 3) + (i & 3);
   const int gph = hd >> 6;
   const int head = grp / gph, qq = grp - head * gph;

@@ -14,8 +14,9 @@
 // v_mfma_f32_32x32x16_bf16 a lane then owns ONE token (column lane%32) and 16 features
 // of each 32x32 block, which makes everything per-token in the epilogue (r_t, position,
 // page, slot) a per-lane scalar.  The packing order of the weight rows (pack kernel)
-// makes those 16 features consecutive in the cache row and puts the two members of
-// every RoPE pair into the same lane and register index of two neighbouring blocks.
+// makes those 16 features consecutive in the cache row, puts the two members of every
+// RoPE pair into the same lane and register index of two neighbouring blocks, and
+// alternates K and V row groups so that every wave has one of each.
 //
 // Tiling.  Workgroup = 512 threads = 8 waves, two per SIMD, arranged 2 (features) x 4
 // (tokens); workgroup tile = 256 features x 256 tokens, wave tile = 128 x 64 (4x2 MFMA
@@ -181,9 +182,7 @@ __global__ __launch_bounds__(kThreads) void restore_kernel(const RestoreArgs a, 
   // ---- per-token lookups, done up front so that their memory latency hides behind the
   // first tile loads.  Lane l32 owns token column l32 of each of its two 32-token blocks:
   // position, (ragged) context, page -> row index of the token in the pool, or -1.
-  const int wave_f0 = tile_f * kTileF + wm * 128;         // first physical weight row of the wave
-  const int part = wave_f0 >= a.d_kv_pad ? 1 : 0;         // 0 = K rows, 1 = V rows (wave-uniform)
-  int pos[2], page[2], tok_row[2];
+  int pos[2], page[2], tok_row[2];                        // tok_row: row of the token's K in the pool
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     const int t = tile_t * kTileT + wn * 64 + j * 32 + l32;
@@ -232,7 +231,7 @@ __global__ __launch_bounds__(kThreads) void restore_kernel(const RestoreArgs a, 
     tok_row[j] = -1;
     if (pos[j] >= 0) {
       if (page[j] < 0 || page[j] >= a.num_pages) atomicOr(a.err, HC_DEV_BAD_PAGE);
-      else tok_row[j] = ((page[j] * 2 + part) << a.block_shift) + (pos[j] & ((1 << a.block_shift) - 1));
+      else tok_row[j] = ((page[j] * 2) << a.block_shift) + (pos[j] & ((1 << a.block_shift) - 1));
     }
   }
   asm volatile("s_waitcnt vmcnt(12)" ::: "memory");      // the first 6 (W0, X0) have landed
@@ -317,40 +316,36 @@ __global__ __launch_bounds__(kThreads) void restore_kernel(const RestoreArgs a, 
 #pragma unroll
     for (int j = 0; j < 2; ++j) rstd[j] = rsqrtf(sums[(wn * 2 + j) * 32 + l32] * a.inv_d + a.eps);
   }
-  const int part_f0 = wave_f0 - part * a.d_kv_pad;
+  // The wave's 128 weight rows are one K pair group (blocks 0, 1) and the V pair group of the
+  // same index (blocks 2, 3).
+  const int grp = (tile_f * kTileF + wm * 128) >> 7;
+  if (grp * kPairGroup >= a.d_kv) return;                 // padding rows only (wave-uniform)
   const int hd = a.head_dim, half = hd >> 1, groups_per_head = hd >> 6;
-  int head[2], i0[2];
-  bool live[2];
+  const int head = grp / groups_per_head;
+  const int i0 = 32 * (grp - head * groups_per_head) + 16 * lh;   // first RoPE pair index of this lane
+  // batches b = 2 j + q: token block j, q = 0 -> K (rotated), q = 1 -> V
+  float4 cs[2][8];                                        // [token block][v / 2]: two (cos, sin) pairs each
+  auto load_cs = [&](int j) {
+    if (tok_row[j] < 0) return;
+    const float2* rope_row = a.rope + (size_t)pos[j] * half + i0;
 #pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    const int grp = (part_f0 >> 6) + q;                   // pair group inside the K or V part
-    live[q] = grp * kPairGroup < a.d_kv;                  // false for padding rows (wave-uniform)
-    head[q] = grp / groups_per_head;
-    i0[q] = 32 * (grp - head[q] * groups_per_head) + 16 * lh;   // first RoPE pair index of this lane
-  }
-  // batches b = 2 j + q: token block j, pair group q
-  float4 cs[2][8];                                        // [buffer][v / 2]: two (cos, sin) pairs each
-  auto load_cs = [&](int b, float4 (&buf)[8]) {
-    const int j = b >> 1, q = b & 1;
-    if (part != 0 || tok_row[j] < 0 || !live[q]) return;
-    const float2* rope_row = a.rope + (size_t)pos[j] * half + i0[q];
-#pragma unroll
-    for (int v = 0; v < 16; v += 2) buf[v >> 1] = *reinterpret_cast<const float4*>(rope_row + v);
+    for (int v = 0; v < 16; v += 2) cs[j][v >> 1] = *reinterpret_cast<const float4*>(rope_row + v);
   };
-  load_cs(0, cs[0]);
+  load_cs(0);
+  load_cs(1);
 #pragma unroll
   for (int b = 0; b < 4; ++b) {
     const int j = b >> 1, q = b & 1;
-    if (b + 1 < 4) load_cs(b + 1, cs[(b + 1) & 1]);
-    if (tok_row[j] < 0 || !live[q]) continue;
-    uint16_t* dst = a.pool + (size_t)tok_row[j] * a.d_kv + head[q] * hd;
+    if (tok_row[j] < 0) continue;
+    // V rows of a page follow its K rows: + block_size token rows
+    uint16_t* dst = a.pool + ((size_t)tok_row[j] + ((size_t)q << a.block_shift)) * a.d_kv + head * hd;
     uint32_t pa[8], pb[8];                                // bf16 pairs of the first / second members
-    if (part == 0) {
+    if (q == 0) {
 #pragma unroll
       for (int v = 0; v < 16; v += 2) {
-        const float4 c4 = cs[b & 1][v >> 1];
-        const float a0 = acc[2 * q][j][v] * rstd[j], b0 = acc[2 * q + 1][j][v] * rstd[j];
-        const float a1 = acc[2 * q][j][v + 1] * rstd[j], b1 = acc[2 * q + 1][j][v + 1] * rstd[j];
+        const float4 c4 = cs[j][v >> 1];
+        const float a0 = acc[0][j][v] * rstd[j], b0 = acc[1][j][v] * rstd[j];
+        const float a1 = acc[0][j][v + 1] * rstd[j], b1 = acc[1][j][v + 1] * rstd[j];
         const float ra0 = a0 * c4.x - b0 * c4.y, rb0 = b0 * c4.x + a0 * c4.y;
         const float ra1 = a1 * c4.z - b1 * c4.w, rb1 = b1 * c4.z + a1 * c4.w;
         if (STYLE == 0) { pa[v >> 1] = pack_bf16x2(ra0, ra1); pb[v >> 1] = pack_bf16x2(rb0, rb1); }
@@ -359,23 +354,23 @@ __global__ __launch_bounds__(kThreads) void restore_kernel(const RestoreArgs a, 
     } else {
 #pragma unroll
       for (int v = 0; v < 16; v += 2) {
-        const float a0 = acc[2 * q][j][v] * rstd[j], b0 = acc[2 * q + 1][j][v] * rstd[j];
-        const float a1 = acc[2 * q][j][v + 1] * rstd[j], b1 = acc[2 * q + 1][j][v + 1] * rstd[j];
+        const float a0 = acc[2][j][v] * rstd[j], b0 = acc[3][j][v] * rstd[j];
+        const float a1 = acc[2][j][v + 1] * rstd[j], b1 = acc[3][j][v + 1] * rstd[j];
         if (STYLE == 0) { pa[v >> 1] = pack_bf16x2(a0, a1); pb[v >> 1] = pack_bf16x2(b0, b1); }
         else            { pa[v >> 1] = pack_bf16x2(a0, b0); pb[v >> 1] = pack_bf16x2(a1, b1); }
       }
     }
     if (STYLE == 0) {
       // first members at head*hd + i, second members at head*hd + hd/2 + i
-      u32x4* da = reinterpret_cast<u32x4*>(dst + i0[q]);
-      u32x4* db = reinterpret_cast<u32x4*>(dst + half + i0[q]);
+      u32x4* da = reinterpret_cast<u32x4*>(dst + i0);
+      u32x4* db = reinterpret_cast<u32x4*>(dst + half + i0);
       da[0] = u32x4{pa[0], pa[1], pa[2], pa[3]};
       da[1] = u32x4{pa[4], pa[5], pa[6], pa[7]};
       db[0] = u32x4{pb[0], pb[1], pb[2], pb[3]};
       db[1] = u32x4{pb[4], pb[5], pb[6], pb[7]};
     } else {
       // members of pair i at head*hd + 2i and 2i + 1: pa/pb hold (first, second) of even/odd v
-      u32x4* dq = reinterpret_cast<u32x4*>(dst + 2 * i0[q]);
+      u32x4* dq = reinterpret_cast<u32x4*>(dst + 2 * i0);
       dq[0] = u32x4{pa[0], pb[0], pa[1], pb[1]};
       dq[1] = u32x4{pa[2], pb[2], pa[3], pb[3]};
       dq[2] = u32x4{pa[4], pb[4], pa[5], pb[5]};
