@@ -25,6 +25,11 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16, vendor figure without sparsity
 
+# HBM-side traffic of one restore_kernel launch, from two rocprofv3 --pmc runs (FETCH_SIZE, then
+# WRITE_SIZE, each scaled by what the counter reads for a plain 256 MiB streaming kernel):
+# profiles/restore_kernel_llama3-8b-gqa-T8192.md.  Bytes per launch; None where not profiled.
+TRAFFIC_BYTES_PER_LAUNCH = {"llama3-8b-gqa-T8192": 2.394e8}
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -67,7 +72,12 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-e2e", action="store_true")
     ap.add_argument("--e2e-steps", type=int, default=5)
+    ap.add_argument("--streams", type=int, default=1,
+                    help="streams the per-layer launches of a step are dealt over (layers are independent)")
     ap.add_argument("--loader", type=int, default=0, help="0 = copy engines, strided runs (default), 1 = gather kernel")
+    ap.add_argument("--zero-inputs", action="store_true",
+                    help="diagnostic: all-zero hidden states and weights (same instruction stream, no "
+                         "operand toggling) to show how far the matrix pipe's clock is power-limited")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB -> 256 MiB streaming kernel three times, so that a "
                          "counter run has a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
@@ -107,6 +117,9 @@ def main():
     with ThreadPoolExecutor(min(16, os.cpu_count() or 8)) as ex:
         gen = list(ex.map(lambda l: (syn.layer_weights(w, l), syn.layer_hidden(w, l)), range(L)))
     for l, ((wkv, gamma), x) in enumerate(gen):
+        if args.zero_inputs:
+            wkv[:] = 0
+            x[:] = 0
         d_w, d_g = dev_bf16(wkv), dev_bf16(gamma)
         ctx.set_layer_weights(l, d_w, d_g, stream)
         torch.cuda.synchronize()
@@ -128,9 +141,13 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    def step():
+    side = [torch.cuda.Stream() for _ in range(args.streams - 1)]
+    lanes = [stream] + [s_.cuda_stream for s_ in side]
+
+    def step(use=None):
+        use = use or lanes
         for l in range(L):
-            ctx.restore_kv(l, hidden_dev[l], d_pos, T, d_bt, len(bt), stream)
+            ctx.restore_kv(l, hidden_dev[l], d_pos, T, d_bt, len(bt), use[l % len(use)])
 
     for _ in range(args.warmup):
         step()
@@ -148,15 +165,17 @@ def main():
     tokens_per_s = T / (ms_per_step * 1e-3)
 
     # ---- dominant kernel: HIP events around every launch, on the launch stream
+    torch.cuda.synchronize()
     ctx.timing_begin()
     for _ in range(max(1, min(args.steps, 4096 // L))):
-        step()
+        step([stream])                                      # one stream: kernels back to back
     avg_ms, launches = ctx.timing_end(stream)
     flop_per_launch = 4.0 * T * d * w.d_kv               # 2 flop per multiply-add, K and V
     achieved = flop_per_launch / (avg_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "restore_kernel", "achieved": round(achieved, 2),
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+                "traffic": None if args.zero_inputs else TRAFFIC_BYTES_PER_LAUNCH.get(w.name),
                 "avg_launch_us": round(avg_ms * 1e3, 2), "launches_timed": launches,
                 "flop_per_launch": flop_per_launch}
     assert ctx.poll_device_error(stream) == 0
@@ -217,10 +236,10 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16",
-        "data": "synthetic",
+        "data": "synthetic" if not args.zero_inputs else "zeros (diagnostic)",
         "config": {"workload": w.name, "layers": L, "d_model": d, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "tokens": T, "block_size": w.block_size,
-                   "hidden_resident_in_hbm": True},
+                   "hidden_resident_in_hbm": True, "launch_streams": args.streams},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "e2e_host_link": e2e,
