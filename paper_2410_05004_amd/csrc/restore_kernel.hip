@@ -179,17 +179,24 @@ __global__ __launch_bounds__(kThreads) void restore_kernel(const RestoreArgs a, 
 
   bf16x8 af0[4], bf0[2], af1[4], bf1[2];
 
-  // ---- per-token lookups, done up front so that their memory latency hides behind the
-  // first tile loads.  Lane l32 owns token column l32 of each of its two 32-token blocks:
-  // position, (ragged) context, page -> row index of the token in the pool, or -1.
-  int pos[2], page[2], tok_row[2];                        // tok_row: row of the token's K in the pool
+  // ---- prologue (18 loads per thread): W0 X0 | W1 X1 | W2 W3 X2(first half), with the
+  // per-token lookups slotted in so that their memory latency hides behind the tile loads.
+  // Lane l32 owns token column l32 of each of its two 32-token blocks: position, (ragged)
+  // context and page are fetched here; the pool row is worked out after the main loop.
+#pragma unroll
+  for (int q = 0; q < 2; ++q) load_w(0, q);
+#pragma unroll
+  for (int hq = 0; hq < 4; ++hq) load_x(0, 0, hq >> 1, hq & 1);
+  __builtin_amdgcn_sched_barrier(0);
+  int pos[2], seq[2], page[2];
+  bool valid[2];                                          // token exists and is mapped so far
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     const int t = tile_t * kTileT + wn * 64 + j * 32 + l32;
-    pos[j] = -1;
-    page[j] = -1;
-    int seq = 0;
-    if (t < a.n_tok) {
+    pos[j] = 0;
+    seq[j] = 0;
+    valid[j] = t < a.n_tok;
+    if (valid[j]) {
       pos[j] = a.positions ? a.positions[t] : a.pos_base + t;
       if (a.cu_seqlens) {                                 // largest s with cu[s] <= t
         int lo = 0, hi = a.n_seq;                         // invariant: cu[lo] <= t < cu[hi]
@@ -197,23 +204,10 @@ __global__ __launch_bounds__(kThreads) void restore_kernel(const RestoreArgs a, 
           const int mid = (lo + hi) >> 1;
           if (a.cu_seqlens[mid] <= t) lo = mid; else hi = mid;
         }
-        seq = lo;
-      }
-      const int blk = pos[j] >> a.block_shift;
-      if (pos[j] < 0 || pos[j] >= a.max_position || blk >= a.max_blocks) {
-        atomicOr(a.err, HC_DEV_BAD_POSITION);
-        pos[j] = -1;
-      } else {
-        page[j] = a.block_tables[(size_t)seq * a.max_blocks + blk];
+        seq[j] = lo;
       }
     }
   }
-  __builtin_amdgcn_sched_barrier(0);
-  // prologue (18 loads per thread): W0 X0 | W1 X1 | W2 W3 X2(first half)
-#pragma unroll
-  for (int q = 0; q < 2; ++q) load_w(0, q);
-#pragma unroll
-  for (int hq = 0; hq < 4; ++hq) load_x(0, 0, hq >> 1, hq & 1);
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int q = 0; q < 2; ++q) load_w(1, q);
@@ -228,12 +222,18 @@ __global__ __launch_bounds__(kThreads) void restore_kernel(const RestoreArgs a, 
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
-    tok_row[j] = -1;
-    if (pos[j] >= 0) {
-      if (page[j] < 0 || page[j] >= a.num_pages) atomicOr(a.err, HC_DEV_BAD_PAGE);
-      else tok_row[j] = ((page[j] * 2) << a.block_shift) + (pos[j] & ((1 << a.block_shift) - 1));
+    page[j] = -1;
+    if (valid[j]) {
+      const int blk = pos[j] >> a.block_shift;
+      if (pos[j] < 0 || pos[j] >= a.max_position || blk >= a.max_blocks) {
+        atomicOr(a.err, HC_DEV_BAD_POSITION);
+        valid[j] = false;
+      } else {
+        page[j] = a.block_tables[(size_t)seq[j] * a.max_blocks + blk];
+      }
     }
   }
+  __builtin_amdgcn_sched_barrier(0);
   asm volatile("s_waitcnt vmcnt(12)" ::: "memory");      // the first 6 (W0, X0) have landed
   __builtin_amdgcn_s_barrier();
 #pragma unroll
@@ -306,6 +306,15 @@ __global__ __launch_bounds__(kThreads) void restore_kernel(const RestoreArgs a, 
   // one round-to-nearest-even conversion to bf16 precedes the 16-byte stores into the
   // token's cache row.  The table reads of token block j + 1 are issued before block j is
   // processed, so their latency overlaps the arithmetic and the stores.
+  int tok_row[2];                                         // row of the token's K in the pool, or -1
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    tok_row[j] = -1;
+    if (valid[j]) {
+      if (page[j] < 0 || page[j] >= a.num_pages) atomicOr(a.err, HC_DEV_BAD_PAGE);
+      else tok_row[j] = ((page[j] * 2) << a.block_shift) + (pos[j] & ((1 << a.block_shift) - 1));
+    }
+  }
   float rstd[2];
   {
     // exchange the sums of squares between the two waves of a token range through LDS
