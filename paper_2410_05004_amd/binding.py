@@ -36,6 +36,14 @@ def _load():
         raise ImportError(
             f"{_LIB_FILE} is missing: build it with `python -m paper_2410_05004_amd.build` "
             "(there is no CPU fallback for the restoration path)")
+    # The device pointers and stream handles this library is handed come from the caller's HIP
+    # runtime, so both must be the same loaded runtime.  PyTorch wheels bundle their own
+    # libamdhip64; when PyTorch is installed, load it first so that libhcache.so binds to that
+    # copy instead of pulling in a second one.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = C.CDLL(_LIB_FILE)
     vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
     p = C.POINTER

@@ -81,11 +81,14 @@ __device__ __forceinline__ void load_to_lds_16(const void* gptr, unsigned char* 
 
 // Tile scheduling.  Workgroup ids are handed to the 8 XCDs round-robin and every XCD has
 // its own L2, so the tiles one XCD works on at the same time should share weight rows
-// and token rows.  The tile grid is cut into super tiles of GF x GT = 32 tiles; super
-// tile k belongs to XCD k % 8.  Workgroups that fall outside the grid exit at once.
+// and token rows.  The tile grid is cut into super tiles of GF x GT tiles (powers of two,
+// GF * GT <= 32 = the CUs of an XCD); super tile k belongs to XCD k % 8.  The host picks the
+// shape that keeps the XCDs evenly loaded first and shares the most rows second.
+// Workgroups that fall outside the grid exit at once.
 struct TileGrid {
   int nf, nt;        // tiles along features / tokens
-  int gf_shift;      // log2(GF); GT = 32 >> gf_shift
+  int gf_shift;      // log2(GF)
+  int g_shift;       // log2(GF * GT)
   int nsf;           // super tiles along features
 };
 
@@ -96,9 +99,9 @@ __global__ __launch_bounds__(kThreads) void restore_kernel(const RestoreArgs a, 
   // ---- which tile
   const int wg = blockIdx.x;
   const int xcd = wg & 7, li = wg >> 3;
-  const int super = (li >> 5) * 8 + xcd, r = li & 31;
+  const int super = (li >> g.g_shift) * 8 + xcd, r = li & ((1 << g.g_shift) - 1);
   const int tile_f = (super % g.nsf) * (1 << g.gf_shift) + (r & ((1 << g.gf_shift) - 1));
-  const int tile_t = (super / g.nsf) * (32 >> g.gf_shift) + (r >> g.gf_shift);
+  const int tile_t = ((super / g.nsf) << (g.g_shift - g.gf_shift)) + (r >> g.gf_shift);
   if (tile_f >= g.nf || tile_t >= g.nt) return;
 
   const int tid = threadIdx.x;
@@ -401,14 +404,26 @@ hipError_t launch_restore(const RestoreArgs& a, hipStream_t stream) {
   TileGrid g;
   g.nf = 2 * a.d_kv_pad / kTileF;
   g.nt = (a.n_tok + kTileT - 1) / kTileT;
-  // super tile shape: as close to square as the feature extent allows (8x4, 4x8, 2x16, 1x32)
-  g.gf_shift = g.nf >= 8 ? 3 : g.nf >= 4 ? 2 : g.nf >= 2 ? 1 : 0;
-  const int gf = 1 << g.gf_shift, gt = 32 >> g.gf_shift;
-  g.nsf = (g.nf + gf - 1) / gf;
-  const int nst = (g.nt + gt - 1) / gt;
-  const int n_super = g.nsf * nst;
-  const int rounds = (n_super + 7) / 8;                   // super tiles per XCD
-  const unsigned grid = (unsigned)rounds * 8u * 32u;
+  // Super-tile shape: fewest rounds on the busiest XCD (an XCD runs 32 workgroups at a
+  // time, one per CU), then the most row sharing (smallest 1/GF + 1/GT), then fewest slots.
+  int best_rounds = 1 << 30, best_slots = 1 << 30, best_share = 1 << 30;
+  g.gf_shift = g.g_shift = 0;
+  for (int fs = 0; fs <= 5; ++fs) {
+    for (int ts = 0; fs + ts <= 5; ++ts) {
+      const int gf = 1 << fs, gt = 1 << ts;
+      const int n_super = ((g.nf + gf - 1) / gf) * ((g.nt + gt - 1) / gt);
+      const int slots = (n_super + 7) / 8 * gf * gt;      // workgroup slots per XCD
+      const int rounds = (slots + 31) / 32;
+      const int share = (32 >> fs) + (32 >> ts);          // 32 * (1/GF + 1/GT)
+      if (rounds < best_rounds || (rounds == best_rounds && share < best_share) ||
+          (rounds == best_rounds && share == best_share && slots < best_slots)) {
+        best_rounds = rounds; best_share = share; best_slots = slots;
+        g.gf_shift = fs; g.g_shift = fs + ts;
+      }
+    }
+  }
+  g.nsf = (g.nf + (1 << g.gf_shift) - 1) >> g.gf_shift;
+  const unsigned grid = (unsigned)best_slots * 8u;
   if (a.rope_style == 0)
     hipLaunchKernelGGL(restore_kernel<0>, dim3(grid), dim3(kThreads), kLdsBytes, stream, a, g);
   else

@@ -1,0 +1,80 @@
+"""Restoration-kernel time against the number of restored tokens (one layer).
+
+The paper rejects a token-wise split of the state because the projection's run time is not
+proportional to the token count: it moves in steps set by the GEMM library's tile sizes
+(Section 4.1.1, "Performance considerations"; Section 6.3.2 shows the measured steps).  This
+script measures the same curve for this library's kernel on MI355X: time per launch for
+n_tok = step, 2*step, ... at a given model shape, so that a scheduler can pick mini-batch
+sizes on the flat part of each step (the kernel's token tile is 256).
+
+    python -m paper_2410_05004_amd.sweep_tokens [--workload 3] [--max-tokens 4096] [--step 64]
+
+Prints one line per token count and a final JSON object; needs a GPU.
+"""
+import argparse
+import json
+import os
+import sys
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", type=int, default=3, help="model shape (default: Llama-2-13B-shaped)")
+    ap.add_argument("--max-tokens", type=int, default=4096)
+    ap.add_argument("--step", type=int, default=64)
+    ap.add_argument("--reps", type=int, default=20)
+    args = ap.parse_args()
+
+    import torch
+    import synthetic as syn
+    import paper_2410_05004_amd as hc
+
+    if not torch.cuda.is_available():
+        sys.exit("sweep_tokens: no GPU visible")
+    w = syn.WORKLOADS[args.workload]
+    T = args.max_tokens
+    desc = hc.ModelDesc(1, w.d_model, w.n_q_heads, w.n_kv_heads, w.head_dim, w.block_size, T, 0,
+                        w.rope_theta, w.rms_eps)
+    ctx = hc.Context(desc)
+    s = torch.cuda.current_stream().cuda_stream
+    wkv, gamma = syn.layer_weights(w, 0)
+    x = syn.layer_hidden(w, 0, T)
+    d_w = torch.from_numpy(wkv.view(np.int16)).cuda()
+    d_g = torch.from_numpy(gamma.view(np.int16)).cuda()
+    d_x = torch.from_numpy(x.view(np.int16)).cuda()
+    ctx.set_layer_weights(0, d_w, d_g, s)
+    n_blocks = (T + w.block_size - 1) // w.block_size
+    pool = torch.zeros((n_blocks, 2, w.block_size, w.n_kv_heads, w.head_dim), dtype=torch.bfloat16, device="cuda")
+    ctx.set_kv_pool(0, pool, n_blocks)
+    d_bt = torch.arange(n_blocks, dtype=torch.int32, device="cuda")
+    d_pos = torch.arange(T, dtype=torch.int32, device="cuda")
+    for _ in range(200):                                    # clocks up
+        ctx.restore_kv(0, d_x, d_pos, T, d_bt, n_blocks, s)
+    torch.cuda.synchronize()
+    rows = []
+    print(f"# {w.name} shape: d_model {w.d_model}, d_kv {w.d_kv}; one layer; time per launch")
+    print("# n_tok   us/launch   TFLOP/s   us per 256 tokens")
+    for n in range(args.step, T + 1, args.step):
+        for _ in range(3):
+            ctx.restore_kv(0, d_x, d_pos, n, d_bt, n_blocks, s)
+        ctx.timing_begin()
+        for _ in range(args.reps):
+            ctx.restore_kv(0, d_x, d_pos, n, d_bt, n_blocks, s)
+        avg_ms, _ = ctx.timing_end(s)
+        us = avg_ms * 1e3
+        tf = 4.0 * n * w.d_model * w.d_kv / (avg_ms * 1e-3) / 1e12
+        rows.append({"n_tok": n, "us": round(us, 2), "tflops": round(tf, 1)})
+        print(f"{n:7d} {us:10.2f} {tf:9.1f} {us * 256 / n:12.2f}", flush=True)
+    assert ctx.poll_device_error(s) == 0
+    print(json.dumps({"workload": w.name, "d_model": w.d_model, "d_kv": w.d_kv, "rows": rows}))
+    ctx.destroy()
+
+
+if __name__ == "__main__":
+    main()
