@@ -61,6 +61,7 @@ enum {
 
 typedef struct hc_ctx hc_ctx;
 typedef struct hc_store hc_store;
+typedef struct hc_saver hc_saver;
 
 /* Shape of the model whose KV cache is restored.  Supported by the kernels:
  * d_model % 64 == 0, head_dim % 64 == 0, block_size a power of two, n_q_heads % n_kv_heads
@@ -185,6 +186,41 @@ hc_status hc_restore_context(hc_ctx* ctx, const hc_store* store, int64_t seq_id,
                              int32_t tok_begin, int32_t n_tok, int32_t pos_offset,
                              const int32_t* d_block_table, int32_t n_blocks,
                              void* compute_stream, void* copy_stream);
+
+/* ---- two-stage saving of new hidden states (Section 4.2.2; Section 5 "Pipelined state
+ * transmission", "Storage management") -------------------------------------------------
+ * Stage 1: the inputs of one layer for the whole running batch (rows of several contexts
+ * under continuous batching) are snapshot with ONE device->host copy into a pinned slot.
+ * Stage 2: daemon threads append each row to the chunk list of its (context, layer) in the
+ * store once the copy has completed.  A context is owned by thread (id mod n_threads), so
+ * its rows reach the store in call order (layer-before-token order is the caller's call
+ * order: layer 0 of a step first).  While a context is being saved its chunks must not be
+ * read; hc_saver_flush makes everything queued so far visible.
+ *   max_rows   largest batch (rows) of one call;  n_slots  snapshots that may be in flight
+ *   before hc_saver_save_layer blocks;  n_threads  daemon threads (the paper uses 8).
+ * The store must outlive the saver.  One producer thread at a time. */
+hc_status hc_saver_create(hc_store* store, int32_t max_rows, int32_t n_slots, int32_t n_threads,
+                          hc_saver** out);
+/* Waits for queued snapshots, stops the daemon threads, frees the slots. */
+hc_status hc_saver_destroy(hc_saver* saver);
+
+/* Snapshot d_hidden (device bf16 [n_rows, d_model], the inputs of `layer` for this step) and
+ * queue it for the daemons; h_row_seq (host int64 [n_rows]) names the context of every row
+ * and is copied by the call.  The copy runs on `down_stream` after everything queued on
+ * `compute_stream` so far; `compute_stream` is made to wait for the copy, so kernels queued
+ * later may overwrite the buffer (the event discipline of Section 5).  Returns once enqueued;
+ * blocks only while all snapshot slots are in flight. */
+hc_status hc_saver_save_layer(hc_saver* saver, int32_t layer, const void* d_hidden, int32_t n_rows,
+                              const int64_t* h_row_seq, void* compute_stream, void* down_stream);
+
+/* Same for rows that already sit in host memory (stage 2 only; works without a GPU). */
+hc_status hc_saver_save_layer_host(hc_saver* saver, int32_t layer, const void* h_rows,
+                                   int32_t n_rows, const int64_t* h_row_seq);
+
+/* Block until every queued snapshot has reached the store.  Returns the first error a
+ * daemon thread met since the last flush (e.g. HC_ERANGE: arena full; HC_ESTATE: layer
+ * order) with its message, else HC_OK. */
+hc_status hc_saver_flush(hc_saver* saver);
 
 /* Loader used by hc_restore_context: 0 (default) = copy engines: chunks of a layer whose
  * arena slots are equally spaced (the usual result of saving in generation order) move in

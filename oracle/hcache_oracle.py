@@ -227,6 +227,15 @@ class ChunkStore:
                                for c in range(self.n_chunks(seq, layer))])
 
 
+def save_step(store, layer, rows, row_seq):
+    """Stage 2 of the two-stage saving (Section 4.2.2): the snapshot of one layer's inputs
+    for the whole running batch is taken apart row by row, each row appended to the chunk
+    list of its own context."""
+    rows = np.asarray(rows)
+    for r, s in zip(rows, row_seq):
+        store.append(int(s), layer, r[None, :])
+
+
 # --------------------------------------------------------------- cost accounting
 def restore_flop(n_tokens, d_model, d_kv):
     """Floating-point operations of one layer's projection, one multiply-add = 2

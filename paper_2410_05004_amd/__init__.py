@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     ModelDesc,
     Context,
     Store,
+    Saver,
     lib,
     lib_path,
     version,

@@ -67,6 +67,11 @@ def _load():
         "hc_store_drop": (i32, [vp, i64]),
         "hc_restore_context": (i32, [vp, vp, i64, i32, i32, i32, vp, i32, vp, vp]),
         "hc_set_loader": (i32, [vp, i32]),
+        "hc_saver_create": (i32, [vp, i32, i32, i32, p(vp)]),
+        "hc_saver_destroy": (i32, [vp]),
+        "hc_saver_save_layer": (i32, [vp, i32, vp, i32, vp, vp, vp]),
+        "hc_saver_save_layer_host": (i32, [vp, i32, vp, i32, vp]),
+        "hc_saver_flush": (i32, [vp]),
         "hc_timing_begin": (i32, [vp]),
         "hc_timing_end": (i32, [vp, vp, p(C.c_double), p(i32)]),
     }
@@ -80,7 +85,9 @@ lib = _load()
 EXPORTED = ("hc_last_error hc_version hc_validate_desc hc_create hc_destroy hc_set_layer_weights "
             "hc_set_kv_pool hc_restore_kv hc_restore_kv_ragged hc_poll_device_error hc_store_create "
             "hc_store_create_ex hc_store_destroy hc_store_append hc_store_tokens hc_store_chunk "
-            "hc_store_drop hc_restore_context hc_set_loader hc_timing_begin hc_timing_end").split()
+            "hc_store_drop hc_restore_context hc_set_loader hc_timing_begin hc_timing_end "
+            "hc_saver_create hc_saver_destroy hc_saver_save_layer hc_saver_save_layer_host "
+            "hc_saver_flush").split()
 
 
 def _check(status):
@@ -200,3 +207,34 @@ class Store:
 
     def drop(self, seq_id):
         _check(lib.hc_store_drop(self._h, seq_id))
+
+
+class Saver:
+    """Owner of an hc_saver* (two-stage saving into a Store)."""
+
+    def __init__(self, store, max_rows, n_slots=4, n_threads=8):
+        h = C.c_void_p()
+        _check(lib.hc_saver_create(store._h, max_rows, n_slots, n_threads, C.byref(h)))
+        self._h = h
+        self._store = store           # keep the store alive
+
+    def destroy(self):
+        if self._h:
+            lib.hc_saver_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def save_layer(self, layer, d_hidden, n_rows, h_row_seq, compute_stream, down_stream):
+        _check(lib.hc_saver_save_layer(self._h, layer, _ptr(d_hidden), n_rows, _ptr(h_row_seq),
+                                       compute_stream, down_stream))
+
+    def save_layer_host(self, layer, h_rows, n_rows, h_row_seq):
+        _check(lib.hc_saver_save_layer_host(self._h, layer, _ptr(h_rows), n_rows, _ptr(h_row_seq)))
+
+    def flush(self):
+        _check(lib.hc_saver_flush(self._h))

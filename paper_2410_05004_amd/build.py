@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhcache.so")
-SOURCES = ["api.cpp", "store.cpp", "restore_kernel.hip", "aux_kernels.hip"]
+SOURCES = ["api.cpp", "store.cpp", "saver.cpp", "restore_kernel.hip", "aux_kernels.hip"]
 
 
 def hipcc_path():
@@ -22,7 +22,7 @@ def build(verbose=False, extra_flags=()):
     """Compile every source for gfx950 and link the shared library. Always recompiles."""
     cmd = [
         hipcc_path(), "-x", "hip", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-        "-Wall", "-Wno-unused-result",
+        "-Wall", "-Wno-unused-result", "-pthread",
         # packed fp32 ALU forms are kept out of the generated code on purpose
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
         "-I", os.path.join(ROOT, "include"), "-I", CSRC,

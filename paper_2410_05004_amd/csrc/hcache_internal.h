@@ -4,7 +4,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <string>
+#include <unordered_map>
 #include <vector>
 
 #include "hcache.h"
@@ -131,4 +133,23 @@ struct hc_ctx {
   bool timing = false;
   std::vector<hipEvent_t> ev_pool;        // created on demand, reused
   int ev_used = 0;
+};
+
+struct hc_seq_state {
+  std::vector<std::vector<int64_t>> chunks;   // per layer: arena chunk slots, in token order
+  std::vector<int64_t> tokens;                // per layer: rows stored
+};
+
+struct hc_store {
+  int32_t n_layers = 0, d_model = 0, chunk_tokens = 0;
+  int64_t capacity_chunks = 0;
+  size_t row_bytes = 0, chunk_bytes = 0;
+  unsigned char* arena = nullptr;
+  bool pinned = false;
+  int64_t next_fresh = 0;                     // chunks [next_fresh, capacity) were never used
+  std::vector<int64_t> free_list;             // returned chunks, reused first
+  std::unordered_map<int64_t, hc_seq_state> seqs;
+  // guards the index (seqs, free_list, next_fresh) when the saver's daemon threads append
+  // concurrently; row payloads are copied outside of it
+  std::mutex index_mutex;
 };

@@ -1,0 +1,301 @@
+// Two-stage saving of newly generated hidden states (paper Section 4.2.2; Section 5,
+// "Pipelined state transmission" and "Storage management").
+//
+// Stage 1 (GPU side): the hidden states of one layer for the whole batch -- rows of several
+// contexts under continuous batching -- are snapshot to pinned host memory with ONE
+// device->host copy on a downstream stream; an event lets the compute stream reuse the
+// activation buffer as soon as the copy has read it.
+// Stage 2 (host side): daemon threads pick the snapshot up once its copy has completed and
+// append every row to the chunk list of its (context, layer) in the store, so the small
+// scattered writes never touch the GPU's critical path.
+//
+// Ordering: the store requires that a layer never runs ahead of the layer below it for the
+// same context.  Snapshots are queued in call order and every context is owned by exactly one
+// daemon thread (context id modulo the thread count), which works through the queue in
+// order; rows of one context are therefore appended in call order, with no lock held on the
+// per-context state beyond the store's index mutex.
+#include <atomic>
+#include <condition_variable>
+#include <cstdlib>
+#include <cstring>
+#include <deque>
+#include <memory>
+#include <new>
+#include <thread>
+
+#include "hcache_internal.h"
+
+using namespace hc;
+
+namespace {
+
+struct SaveJob {
+  int slot = -1;
+  int32_t layer = 0;
+  int32_t n_rows = 0;
+  std::vector<int64_t> row_seq;
+  hipEvent_t copied = nullptr;      // null: rows were already on the host
+  std::atomic<int> workers_left{0};
+};
+
+}  // namespace
+
+struct hc_saver {
+  hc_store* store = nullptr;
+  int32_t max_rows = 0, n_slots = 0, n_threads = 0;
+  int device = -1;                  // -1: created without a GPU (host rows only)
+  size_t row_bytes = 0;
+  std::vector<unsigned char*> slot_buf;
+  std::vector<bool> slot_pinned;
+  std::vector<hipEvent_t> ev_ready;   // recorded on the compute stream, waited by the downstream stream
+  std::vector<hipEvent_t> ev_copied;  // recorded on the downstream stream after the snapshot copy
+  std::vector<char> slot_busy;
+
+  std::mutex m;
+  std::condition_variable cv_work, cv_idle;
+  std::vector<std::deque<std::shared_ptr<SaveJob>>> queues;   // one per daemon thread
+  std::vector<std::thread> threads;
+  bool stopping = false;
+  int64_t jobs_in_flight = 0;
+  hc_status first_error = HC_OK;
+  std::string first_error_msg;
+};
+
+static void daemon_main(hc_saver* sv, int tid) {
+  if (sv->device >= 0) (void)hipSetDevice(sv->device);
+  for (;;) {
+    std::shared_ptr<SaveJob> job;
+    {
+      std::unique_lock<std::mutex> lock(sv->m);
+      sv->cv_work.wait(lock, [&] { return sv->stopping || !sv->queues[tid].empty(); });
+      if (sv->queues[tid].empty()) return;             // stopping and drained
+      job = sv->queues[tid].front();
+      sv->queues[tid].pop_front();
+    }
+    hc_status err = HC_OK;
+    std::string msg;
+    if (job->copied) {
+      hipError_t e = hipEventSynchronize(job->copied);
+      if (e != hipSuccess) {
+        err = HC_EHIP;
+        msg = std::string("hipEventSynchronize in the save daemon: ") + hipGetErrorString(e);
+      }
+    }
+    if (err == HC_OK) {
+      const unsigned char* rows = sv->slot_buf[job->slot];
+      int i = 0;
+      while (i < job->n_rows) {
+        const int64_t seq = job->row_seq[i];
+        int j = i + 1;
+        while (j < job->n_rows && job->row_seq[j] == seq) ++j;   // run of rows of one context
+        const int64_t owner = ((seq % sv->n_threads) + sv->n_threads) % sv->n_threads;
+        if (owner == tid) {
+          hc_status r = hc_store_append(sv->store, seq, job->layer, rows + (size_t)i * sv->row_bytes, j - i);
+          if (r != HC_OK && err == HC_OK) {
+            err = r;
+            msg = hc_last_error();
+          }
+        }
+        i = j;
+      }
+    }
+    {
+      std::lock_guard<std::mutex> lock(sv->m);
+      if (err != HC_OK && sv->first_error == HC_OK) {
+        sv->first_error = err;
+        sv->first_error_msg = msg;
+      }
+      if (job->workers_left.fetch_sub(1) == 1) {
+        sv->slot_busy[job->slot] = 0;
+        --sv->jobs_in_flight;
+        sv->cv_idle.notify_all();
+      }
+    }
+  }
+}
+
+// Take a free snapshot slot (blocks while all are in use: back-pressure on the producer).
+static int acquire_slot(hc_saver* sv) {
+  std::unique_lock<std::mutex> lock(sv->m);
+  for (;;) {
+    for (int s = 0; s < sv->n_slots; ++s)
+      if (!sv->slot_busy[s]) {
+        sv->slot_busy[s] = 1;
+        ++sv->jobs_in_flight;
+        return s;
+      }
+    sv->cv_idle.wait(lock);
+  }
+}
+
+static void submit(hc_saver* sv, const std::shared_ptr<SaveJob>& job) {
+  job->workers_left.store(sv->n_threads);
+  {
+    std::lock_guard<std::mutex> lock(sv->m);
+    for (auto& q : sv->queues) q.push_back(job);
+  }
+  sv->cv_work.notify_all();
+}
+
+static hc_status check_save_args(hc_saver* sv, int32_t layer, const void* rows, int32_t n_rows,
+                                 const int64_t* h_row_seq) {
+  if (!sv) return fail(HC_EINVAL, "saver is null");
+  if (layer < 0 || layer >= sv->store->n_layers) return fail(HC_ERANGE, "layer out of range");
+  if (n_rows < 0) return fail(HC_EINVAL, "negative row count");
+  if (n_rows > sv->max_rows) return fail(HC_ERANGE, "batch larger than the saver's max_rows");
+  if (n_rows > 0 && (!rows || !h_row_seq)) return fail(HC_EINVAL, "null pointer");
+  return HC_OK;
+}
+
+extern "C" {
+
+hc_status hc_saver_create(hc_store* store, int32_t max_rows, int32_t n_slots, int32_t n_threads,
+                          hc_saver** out) {
+  clear_error();
+  if (!out) return fail(HC_EINVAL, "out is null");
+  *out = nullptr;
+  if (!store) return fail(HC_EINVAL, "store is null");
+  if (max_rows <= 0 || n_slots <= 0 || n_threads <= 0 || n_threads > 64 || n_slots > 1024)
+    return fail(HC_EINVAL, "max_rows, n_slots must be positive; n_threads in 1..64");
+  hc_saver* sv = new (std::nothrow) hc_saver();
+  if (!sv) return fail(HC_ENOMEM, "out of host memory");
+  sv->store = store;
+  sv->max_rows = max_rows;
+  sv->n_slots = n_slots;
+  sv->n_threads = n_threads;
+  sv->row_bytes = store->row_bytes;
+  int dev = -1;
+  if (hipGetDevice(&dev) == hipSuccess) sv->device = dev;
+  else (void)hipGetLastError();
+  const size_t bytes = (size_t)max_rows * sv->row_bytes;
+  bool ok = true;
+  for (int s = 0; s < n_slots && ok; ++s) {
+    void* p = nullptr;
+    bool pinned = false;
+    if (sv->device >= 0 && hipHostMalloc(&p, bytes, hipHostMallocDefault) == hipSuccess) {
+      pinned = true;
+    } else {
+      (void)hipGetLastError();
+      p = nullptr;
+      if (sv->device >= 0 || posix_memalign(&p, 4096, bytes) != 0) ok = false;   // a GPU host must pin
+    }
+    if (!ok) break;
+    sv->slot_buf.push_back(static_cast<unsigned char*>(p));
+    sv->slot_pinned.push_back(pinned);
+    hipEvent_t a = nullptr, b = nullptr;
+    if (sv->device >= 0) {
+      if (hipEventCreateWithFlags(&a, hipEventDisableTiming) != hipSuccess ||
+          hipEventCreateWithFlags(&b, hipEventDisableTiming) != hipSuccess)
+        ok = false;
+    }
+    sv->ev_ready.push_back(a);
+    sv->ev_copied.push_back(b);
+  }
+  if (!ok) {
+    (void)hipGetLastError();
+    for (size_t s = 0; s < sv->slot_buf.size(); ++s) {
+      if (sv->slot_pinned[s]) (void)hipHostFree(sv->slot_buf[s]); else free(sv->slot_buf[s]);
+      if (sv->ev_ready[s]) (void)hipEventDestroy(sv->ev_ready[s]);
+      if (sv->ev_copied[s]) (void)hipEventDestroy(sv->ev_copied[s]);
+    }
+    delete sv;
+    return fail(HC_ENOMEM, "allocation of the snapshot slots failed");
+  }
+  sv->slot_busy.assign(n_slots, 0);
+  sv->queues.resize(n_threads);
+  for (int t = 0; t < n_threads; ++t) sv->threads.emplace_back(daemon_main, sv, t);
+  *out = sv;
+  return HC_OK;
+}
+
+hc_status hc_saver_flush(hc_saver* sv) {
+  clear_error();
+  if (!sv) return fail(HC_EINVAL, "saver is null");
+  std::unique_lock<std::mutex> lock(sv->m);
+  sv->cv_idle.wait(lock, [&] { return sv->jobs_in_flight == 0; });
+  if (sv->first_error != HC_OK) {
+    const hc_status e = sv->first_error;
+    const std::string msg = "save daemon: " + sv->first_error_msg;
+    sv->first_error = HC_OK;
+    sv->first_error_msg.clear();
+    return fail(e, msg);
+  }
+  return HC_OK;
+}
+
+hc_status hc_saver_destroy(hc_saver* sv) {
+  clear_error();
+  if (!sv) return HC_OK;
+  {
+    std::unique_lock<std::mutex> lock(sv->m);
+    sv->cv_idle.wait(lock, [&] { return sv->jobs_in_flight == 0; });
+    sv->stopping = true;
+  }
+  sv->cv_work.notify_all();
+  for (auto& t : sv->threads) t.join();
+  for (size_t s = 0; s < sv->slot_buf.size(); ++s) {
+    if (sv->slot_pinned[s]) (void)hipHostFree(sv->slot_buf[s]); else free(sv->slot_buf[s]);
+    if (sv->ev_ready[s]) (void)hipEventDestroy(sv->ev_ready[s]);
+    if (sv->ev_copied[s]) (void)hipEventDestroy(sv->ev_copied[s]);
+  }
+  delete sv;
+  return HC_OK;
+}
+
+hc_status hc_saver_save_layer(hc_saver* sv, int32_t layer, const void* d_hidden, int32_t n_rows,
+                              const int64_t* h_row_seq, void* compute_stream, void* down_stream) {
+  clear_error();
+  hc_status s = check_save_args(sv, layer, d_hidden, n_rows, h_row_seq);
+  if (s != HC_OK) return s;
+  if (n_rows == 0) return HC_OK;
+  if (sv->device < 0) return fail(HC_ESTATE, "saver was created without a GPU");
+  if (compute_stream == down_stream) return fail(HC_EINVAL, "compute and downstream streams must differ");
+  hipStream_t cs = static_cast<hipStream_t>(compute_stream);
+  hipStream_t ds = static_cast<hipStream_t>(down_stream);
+  const int slot = acquire_slot(sv);
+  auto release = [&] {
+    std::lock_guard<std::mutex> lock(sv->m);
+    sv->slot_busy[slot] = 0;
+    --sv->jobs_in_flight;
+    sv->cv_idle.notify_all();
+  };
+  hipError_t e = hipEventRecord(sv->ev_ready[slot], cs);           // the layer's input is complete here
+  if (e == hipSuccess) e = hipStreamWaitEvent(ds, sv->ev_ready[slot], 0);
+  if (e == hipSuccess)
+    e = hipMemcpyAsync(sv->slot_buf[slot], d_hidden, (size_t)n_rows * sv->row_bytes,
+                       hipMemcpyDeviceToHost, ds);                // ONE copy for the whole batch
+  if (e == hipSuccess) e = hipEventRecord(sv->ev_copied[slot], ds);
+  // later work on the compute stream may overwrite the activation buffer only after the copy
+  if (e == hipSuccess) e = hipStreamWaitEvent(cs, sv->ev_copied[slot], 0);
+  if (e != hipSuccess) {
+    release();
+    return fail_hip(e, "hc_saver_save_layer");
+  }
+  auto job = std::make_shared<SaveJob>();
+  job->slot = slot;
+  job->layer = layer;
+  job->n_rows = n_rows;
+  job->row_seq.assign(h_row_seq, h_row_seq + n_rows);
+  job->copied = sv->ev_copied[slot];
+  submit(sv, job);
+  return HC_OK;
+}
+
+hc_status hc_saver_save_layer_host(hc_saver* sv, int32_t layer, const void* h_rows, int32_t n_rows,
+                                   const int64_t* h_row_seq) {
+  clear_error();
+  hc_status s = check_save_args(sv, layer, h_rows, n_rows, h_row_seq);
+  if (s != HC_OK) return s;
+  if (n_rows == 0) return HC_OK;
+  const int slot = acquire_slot(sv);
+  memcpy(sv->slot_buf[slot], h_rows, (size_t)n_rows * sv->row_bytes);
+  auto job = std::make_shared<SaveJob>();
+  job->slot = slot;
+  job->layer = layer;
+  job->n_rows = n_rows;
+  job->row_seq.assign(h_row_seq, h_row_seq + n_rows);
+  submit(sv, job);
+  return HC_OK;
+}
+
+}  // extern "C"

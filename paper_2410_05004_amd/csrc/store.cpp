@@ -4,25 +4,8 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
-#include <unordered_map>
 
 #include "hcache_internal.h"
-
-struct hc_seq_state {
-  std::vector<std::vector<int64_t>> chunks;   // per layer: arena chunk slots, in token order
-  std::vector<int64_t> tokens;                // per layer: rows stored
-};
-
-struct hc_store {
-  int32_t n_layers = 0, d_model = 0, chunk_tokens = 0;
-  int64_t capacity_chunks = 0;
-  size_t row_bytes = 0, chunk_bytes = 0;
-  unsigned char* arena = nullptr;
-  bool pinned = false;
-  int64_t next_fresh = 0;                     // chunks [next_fresh, capacity) were never used
-  std::vector<int64_t> free_list;             // returned chunks, reused first
-  std::unordered_map<int64_t, hc_seq_state> seqs;
-};
 
 using namespace hc;
 
@@ -92,46 +75,63 @@ hc_status hc_store_append(hc_store* st, int64_t seq_id, int32_t layer, const voi
   if (n_tok < 0) return fail(HC_EINVAL, "negative token count");
   if (n_tok == 0) return HC_OK;
   if (!h_rows) return fail(HC_EINVAL, "rows pointer is null");
-  auto it = st->seqs.find(seq_id);
-  if (it == st->seqs.end()) {
-    hc_seq_state s;
-    s.chunks.resize(st->n_layers);
-    s.tokens.assign(st->n_layers, 0);
-    it = st->seqs.emplace(seq_id, std::move(s)).first;
-  }
-  hc_seq_state& s = it->second;
-  // generation order: a layer never holds more tokens than the layer below it
-  if (layer > 0 && s.tokens[layer - 1] < s.tokens[layer] + n_tok)
-    return fail(HC_ESTATE, "layer appended before the layer below it (layer-before-token order)");
-  // make sure the arena can take the whole append before touching anything
-  const int64_t have = (int64_t)s.chunks[layer].size() * st->chunk_tokens - s.tokens[layer];
-  const int64_t need_rows = n_tok > have ? n_tok - have : 0;
-  const int64_t need_chunks = (need_rows + st->chunk_tokens - 1) / st->chunk_tokens;
-  const int64_t avail = (int64_t)st->free_list.size() + (st->capacity_chunks - st->next_fresh);
-  if (need_chunks > avail) return fail(HC_ERANGE, "chunk arena is full");
-
-  const unsigned char* src = static_cast<const unsigned char*>(h_rows);
-  int32_t left = n_tok;
-  while (left > 0) {
-    const int64_t fill = s.tokens[layer] % st->chunk_tokens;
-    if (fill == 0 && s.tokens[layer] == (int64_t)s.chunks[layer].size() * st->chunk_tokens) {
-      int64_t slot;
-      if (!st->free_list.empty()) {
-        slot = st->free_list.back();
-        st->free_list.pop_back();
-      } else {
-        slot = st->next_fresh++;
-      }
-      s.chunks[layer].push_back(slot);
+  // Index update under the lock (the saver's daemon threads append concurrently); the row
+  // payload is copied afterwards, outside of it.
+  struct Piece { unsigned char* dst; size_t src_off, bytes; };
+  Piece pieces_small[8];
+  std::vector<Piece> pieces_big;
+  int n_pieces = 0;
+  {
+    std::lock_guard<std::mutex> lock(st->index_mutex);
+    auto it = st->seqs.find(seq_id);
+    if (it == st->seqs.end()) {
+      hc_seq_state fresh;
+      fresh.chunks.resize(st->n_layers);
+      fresh.tokens.assign(st->n_layers, 0);
+      it = st->seqs.emplace(seq_id, std::move(fresh)).first;
     }
-    const int64_t room = st->chunk_tokens - fill;
-    const int32_t take = left < room ? left : (int32_t)room;
-    unsigned char* dst = st->arena + (size_t)s.chunks[layer].back() * st->chunk_bytes +
-                         (size_t)fill * st->row_bytes;
-    memcpy(dst, src, (size_t)take * st->row_bytes);
-    src += (size_t)take * st->row_bytes;
-    s.tokens[layer] += take;
-    left -= take;
+    hc_seq_state& s = it->second;
+    // generation order: a layer never holds more tokens than the layer below it
+    if (layer > 0 && s.tokens[layer - 1] < s.tokens[layer] + n_tok)
+      return fail(HC_ESTATE, "layer appended before the layer below it (layer-before-token order)");
+    // make sure the arena can take the whole append before touching anything
+    const int64_t have = (int64_t)s.chunks[layer].size() * st->chunk_tokens - s.tokens[layer];
+    const int64_t need_rows = n_tok > have ? n_tok - have : 0;
+    const int64_t need_chunks = (need_rows + st->chunk_tokens - 1) / st->chunk_tokens;
+    const int64_t avail = (int64_t)st->free_list.size() + (st->capacity_chunks - st->next_fresh);
+    if (need_chunks > avail) return fail(HC_ERANGE, "chunk arena is full");
+
+    size_t src_off = 0;
+    int32_t left = n_tok;
+    while (left > 0) {
+      const int64_t fill = s.tokens[layer] % st->chunk_tokens;
+      if (fill == 0 && s.tokens[layer] == (int64_t)s.chunks[layer].size() * st->chunk_tokens) {
+        int64_t slot;
+        if (!st->free_list.empty()) {
+          slot = st->free_list.back();
+          st->free_list.pop_back();
+        } else {
+          slot = st->next_fresh++;
+        }
+        s.chunks[layer].push_back(slot);
+      }
+      const int64_t room = st->chunk_tokens - fill;
+      const int32_t take = left < room ? left : (int32_t)room;
+      Piece pc;
+      pc.dst = st->arena + (size_t)s.chunks[layer].back() * st->chunk_bytes + (size_t)fill * st->row_bytes;
+      pc.src_off = src_off;
+      pc.bytes = (size_t)take * st->row_bytes;
+      if (n_pieces < 8) pieces_small[n_pieces] = pc; else pieces_big.push_back(pc);
+      ++n_pieces;
+      src_off += pc.bytes;
+      s.tokens[layer] += take;
+      left -= take;
+    }
+  }
+  const unsigned char* src = static_cast<const unsigned char*>(h_rows);
+  for (int i = 0; i < n_pieces; ++i) {
+    const Piece& pc = i < 8 ? pieces_small[i] : pieces_big[i - 8];
+    memcpy(pc.dst, src + pc.src_off, pc.bytes);
   }
   return HC_OK;
 }
@@ -161,6 +161,7 @@ hc_status hc_store_chunk(const hc_store* st, int64_t seq_id, int32_t layer, int3
 hc_status hc_store_drop(hc_store* st, int64_t seq_id) {
   clear_error();
   if (!st) return fail(HC_EINVAL, "store is null");
+  std::lock_guard<std::mutex> lock(st->index_mutex);
   auto it = st->seqs.find(seq_id);
   if (it == st->seqs.end()) return fail(HC_ERANGE, "unknown context");
   for (auto& per_layer : it->second.chunks)

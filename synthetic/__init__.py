@@ -16,6 +16,7 @@ from .workloads import (
     ragged_lengths,
     ragged_block_tables,
     dense_model_weights,
+    batching_schedule,
 )
 
 __all__ = [
@@ -31,4 +32,5 @@ __all__ = [
     "ragged_lengths",
     "ragged_block_tables",
     "dense_model_weights",
+    "batching_schedule",
 ]

@@ -163,3 +163,32 @@ def dense_model_weights(w, layer):
         "w_down": _normal_bf16(r, (w.d_model, w.d_ff), 0.0, 0.02),
         "gamma2": _normal_bf16(r, (w.d_model,), 1.0, 0.1),
     }
+
+
+def batching_schedule(seed, n_seq=5, len_range=(40, 300), prefill_chunk=128, max_decode=24):
+    """A seeded continuous-batching schedule (the shape of the paper's serving loop: chunked
+    prefill fused with decode steps): a list of steps, each a list of (context id, first token,
+    number of new tokens).  Contexts join one after another; a context first prefills its
+    prompt in chunks of at most `prefill_chunk` tokens, then decodes one token per step."""
+    rng = np.random.default_rng([BASE_SEED, 977, seed])
+    prompt = rng.integers(len_range[0], len_range[1], size=n_seq, endpoint=True)
+    decode = rng.integers(1, max_decode, size=n_seq, endpoint=True)
+    start = np.sort(rng.integers(0, 6, size=n_seq))          # step at which each context arrives
+    done = np.zeros(n_seq, dtype=np.int64)
+    steps, t = [], 0
+    while np.any(done < prompt + decode):
+        step = []
+        for s in range(n_seq):
+            if t < start[s] or done[s] >= prompt[s] + decode[s]:
+                continue
+            if done[s] < prompt[s]:
+                n = int(min(prefill_chunk, prompt[s] - done[s]))
+            else:
+                n = 1
+            step.append((int(s) * 7 + 3, int(done[s]), n))    # sparse, non-contiguous ids
+            done[s] += n
+        if step:
+            steps.append(step)
+        t += 1
+    totals = {int(s) * 7 + 3: int(prompt[s] + decode[s]) for s in range(n_seq)}
+    return steps, totals

@@ -386,6 +386,22 @@ def check_store(o):
         raise AssertionError("layer order not enforced")
 
 
+def check_save_step(o):
+    """Two-stage saving, stage 2: a batch snapshot holds rows of several contexts; each context
+    must end up with exactly its own rows, in batch order, per layer."""
+    st = o.ChunkStore(2, 2, 2)
+    a = np.array([[1, 1], [2, 2], [3, 3]])
+    b = np.array([[7, 7], [8, 8]])
+    batch = np.array([a[0], b[0], b[1], a[1], a[2]])
+    seq = [10, 20, 20, 10, 10]
+    for layer in range(2):
+        o.save_step(st, layer, batch + 100 * layer, seq)
+    for layer in range(2):
+        assert np.array_equal(st.layer(10, layer), a + 100 * layer)
+        assert np.array_equal(st.layer(20, layer), b + 100 * layer)
+    assert st.n_chunks(10, 0) == 2 and st.chunk(10, 0, 1).shape == (1, 2)
+
+
 # --------------------------------------------------------------- cost accounting
 def check_cost_accounting(o):
     g = golden_constants()
@@ -415,5 +431,6 @@ ALL_CHECKS = (
     check_projection_reduces_to_matmul,
     check_ragged,
     check_store,
+    check_save_step,
     check_cost_accounting,
 )

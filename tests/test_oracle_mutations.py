@@ -130,6 +130,11 @@ def mut_store_row_major_across_layers(o):
     o.ChunkStore.chunk = chunk
 
 
+def mut_save_rows_to_wrong_context(o):
+    real = o.save_step
+    o.save_step = lambda store, layer, rows, row_seq: real(store, layer, rows, list(row_seq)[::-1])
+
+
 def mut_flop_count(o):
     o.restore_flop = lambda n, d, dkv: 2 * n * d * dkv
 
