@@ -191,11 +191,12 @@ hc_status hc_restore_context(hc_ctx* ctx, const hc_store* store, int64_t seq_id,
  * transmission", "Storage management") -------------------------------------------------
  * Stage 1: the inputs of one layer for the whole running batch (rows of several contexts
  * under continuous batching) are snapshot with ONE device->host copy into a pinned slot.
- * Stage 2: daemon threads append each row to the chunk list of its (context, layer) in the
- * store once the copy has completed.  A context is owned by thread (id mod n_threads), so
- * its rows reach the store in call order (layer-before-token order is the caller's call
- * order: layer 0 of a step first).  While a context is being saved its chunks must not be
- * read; hc_saver_flush makes everything queued so far visible.
+ * Stage 2: the save call itself books the rows into the chunk lists of their (context,
+ * layer) -- order rule, capacity and chunk slots, in call order (layer-before-token order is
+ * the caller's call order: layer 0 of a step first) -- and daemon threads copy the rows into
+ * those places once the snapshot copy has completed, piece i on thread i mod n_threads.
+ * While a context is being saved its chunks must not be read; hc_saver_flush makes
+ * everything queued so far visible.
  *   max_rows   largest batch (rows) of one call;  n_slots  snapshots that may be in flight
  *   before hc_saver_save_layer blocks;  n_threads  daemon threads (the paper uses 8).
  * The store must outlive the saver.  One producer thread at a time. */
@@ -209,7 +210,10 @@ hc_status hc_saver_destroy(hc_saver* saver);
  * and is copied by the call.  The copy runs on `down_stream` after everything queued on
  * `compute_stream` so far; `compute_stream` is made to wait for the copy, so kernels queued
  * later may overwrite the buffer (the event discipline of Section 5).  Returns once enqueued;
- * blocks only while all snapshot slots are in flight. */
+ * blocks only while all snapshot slots are in flight.  HC_ERANGE when the arena cannot take
+ * the batch, HC_ESTATE when a layer would run ahead of the layer below it: then nothing of
+ * the batch is queued (rows of contexts booked before the failing one stay counted: drop
+ * those contexts). */
 hc_status hc_saver_save_layer(hc_saver* saver, int32_t layer, const void* d_hidden, int32_t n_rows,
                               const int64_t* h_row_seq, void* compute_stream, void* down_stream);
 
@@ -218,8 +222,8 @@ hc_status hc_saver_save_layer_host(hc_saver* saver, int32_t layer, const void* h
                                    int32_t n_rows, const int64_t* h_row_seq);
 
 /* Block until every queued snapshot has reached the store.  Returns the first error a
- * daemon thread met since the last flush (e.g. HC_ERANGE: arena full; HC_ESTATE: layer
- * order) with its message, else HC_OK. */
+ * daemon thread met since the last flush (a failed wait for the snapshot copy) with its
+ * message, else HC_OK. */
 hc_status hc_saver_flush(hc_saver* saver);
 
 /* Loader used by hc_restore_context: 0 (default) = copy engines: chunks of a layer whose

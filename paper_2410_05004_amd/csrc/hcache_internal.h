@@ -153,3 +153,13 @@ struct hc_store {
   // concurrently; row payloads are copied outside of it
   std::mutex index_mutex;
 };
+
+namespace hc {
+// One contiguous destination of appended rows: `bytes` from offset `src_off` of the source.
+struct StorePiece {
+  unsigned char* dst;
+  size_t src_off, bytes;
+};
+hc_status store_reserve(hc_store* st, int64_t seq_id, int32_t layer, int32_t n_tok,
+                        std::vector<StorePiece>& pieces);
+}  // namespace hc

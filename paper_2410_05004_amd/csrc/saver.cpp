@@ -9,11 +9,12 @@
 // append every row to the chunk list of its (context, layer) in the store, so the small
 // scattered writes never touch the GPU's critical path.
 //
-// Ordering: the store requires that a layer never runs ahead of the layer below it for the
-// same context.  Snapshots are queued in call order and every context is owned by exactly one
-// daemon thread (context id modulo the thread count), which works through the queue in
-// order; rows of one context are therefore appended in call order, with no lock held on the
-// per-context state beyond the store's index mutex.
+// Ordering and balance: the index half of the append (order rule, capacity, chunk slots) is
+// done by the producer inside the save call, in call order, so errors surface there and the
+// daemons never contend on per-context state.  What is queued is a list of contiguous pieces
+// (destination in the arena, offset in the snapshot); piece i is copied by daemon thread
+// i mod n_threads once the snapshot's copy event has fired, so a long prefill of a single
+// context is spread over all threads just like a decode step of many contexts.
 #include <atomic>
 #include <condition_variable>
 #include <cstdlib>
@@ -31,9 +32,7 @@ namespace {
 
 struct SaveJob {
   int slot = -1;
-  int32_t layer = 0;
-  int32_t n_rows = 0;
-  std::vector<int64_t> row_seq;
+  std::vector<StorePiece> pieces;    // where the rows go; src_off is relative to the slot
   hipEvent_t copied = nullptr;      // null: rows were already on the host
   std::atomic<int> workers_left{0};
 };
@@ -83,20 +82,9 @@ static void daemon_main(hc_saver* sv, int tid) {
     }
     if (err == HC_OK) {
       const unsigned char* rows = sv->slot_buf[job->slot];
-      int i = 0;
-      while (i < job->n_rows) {
-        const int64_t seq = job->row_seq[i];
-        int j = i + 1;
-        while (j < job->n_rows && job->row_seq[j] == seq) ++j;   // run of rows of one context
-        const int64_t owner = ((seq % sv->n_threads) + sv->n_threads) % sv->n_threads;
-        if (owner == tid) {
-          hc_status r = hc_store_append(sv->store, seq, job->layer, rows + (size_t)i * sv->row_bytes, j - i);
-          if (r != HC_OK && err == HC_OK) {
-            err = r;
-            msg = hc_last_error();
-          }
-        }
-        i = j;
+      for (size_t i = tid; i < job->pieces.size(); i += sv->n_threads) {
+        const StorePiece& pc = job->pieces[i];
+        memcpy(pc.dst, rows + pc.src_off, pc.bytes);
       }
     }
     {
@@ -144,6 +132,24 @@ static hc_status check_save_args(hc_saver* sv, int32_t layer, const void* rows, 
   if (n_rows < 0) return fail(HC_EINVAL, "negative row count");
   if (n_rows > sv->max_rows) return fail(HC_ERANGE, "batch larger than the saver's max_rows");
   if (n_rows > 0 && (!rows || !h_row_seq)) return fail(HC_EINVAL, "null pointer");
+  return HC_OK;
+}
+
+// Index half of the save, in the producer thread: one reservation per run of rows of the same
+// context.  On failure nothing of this batch is queued (rows reserved before the failing run
+// stay counted in the store: the context's saved state is then incomplete and should be dropped).
+static hc_status reserve_batch(hc_saver* sv, int32_t layer, int32_t n_rows, const int64_t* row_seq,
+                               std::vector<StorePiece>& pieces) {
+  int i = 0;
+  while (i < n_rows) {
+    int j = i + 1;
+    while (j < n_rows && row_seq[j] == row_seq[i]) ++j;
+    const size_t first = pieces.size();
+    hc_status r = store_reserve(sv->store, row_seq[i], layer, j - i, pieces);
+    if (r != HC_OK) return r;
+    for (size_t p = first; p < pieces.size(); ++p) pieces[p].src_off += (size_t)i * sv->row_bytes;
+    i = j;
+  }
   return HC_OK;
 }
 
@@ -252,6 +258,9 @@ hc_status hc_saver_save_layer(hc_saver* sv, int32_t layer, const void* d_hidden,
   if (compute_stream == down_stream) return fail(HC_EINVAL, "compute and downstream streams must differ");
   hipStream_t cs = static_cast<hipStream_t>(compute_stream);
   hipStream_t ds = static_cast<hipStream_t>(down_stream);
+  auto job = std::make_shared<SaveJob>();
+  s = reserve_batch(sv, layer, n_rows, h_row_seq, job->pieces);
+  if (s != HC_OK) return s;
   const int slot = acquire_slot(sv);
   auto release = [&] {
     std::lock_guard<std::mutex> lock(sv->m);
@@ -271,11 +280,7 @@ hc_status hc_saver_save_layer(hc_saver* sv, int32_t layer, const void* d_hidden,
     release();
     return fail_hip(e, "hc_saver_save_layer");
   }
-  auto job = std::make_shared<SaveJob>();
   job->slot = slot;
-  job->layer = layer;
-  job->n_rows = n_rows;
-  job->row_seq.assign(h_row_seq, h_row_seq + n_rows);
   job->copied = sv->ev_copied[slot];
   submit(sv, job);
   return HC_OK;
@@ -287,13 +292,12 @@ hc_status hc_saver_save_layer_host(hc_saver* sv, int32_t layer, const void* h_ro
   hc_status s = check_save_args(sv, layer, h_rows, n_rows, h_row_seq);
   if (s != HC_OK) return s;
   if (n_rows == 0) return HC_OK;
+  auto job = std::make_shared<SaveJob>();
+  s = reserve_batch(sv, layer, n_rows, h_row_seq, job->pieces);
+  if (s != HC_OK) return s;
   const int slot = acquire_slot(sv);
   memcpy(sv->slot_buf[slot], h_rows, (size_t)n_rows * sv->row_bytes);
-  auto job = std::make_shared<SaveJob>();
   job->slot = slot;
-  job->layer = layer;
-  job->n_rows = n_rows;
-  job->row_seq.assign(h_row_seq, h_row_seq + n_rows);
   submit(sv, job);
   return HC_OK;
 }

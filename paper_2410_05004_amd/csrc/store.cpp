@@ -67,6 +67,66 @@ hc_status hc_store_destroy(hc_store* st) {
   return HC_OK;
 }
 
+}  // extern "C"
+
+namespace hc {
+
+// Index half of an append: under the store's lock, check the order rule and the capacity, take
+// chunk slots and advance the token count of (seq_id, layer) by n_tok; report where the rows
+// go.  The caller copies the payload afterwards (no lock needed: the pieces are its own).
+hc_status store_reserve(hc_store* st, int64_t seq_id, int32_t layer, int32_t n_tok,
+                        std::vector<StorePiece>& pieces) {
+  std::lock_guard<std::mutex> lock(st->index_mutex);
+  auto it = st->seqs.find(seq_id);
+  if (it == st->seqs.end()) {
+    hc_seq_state fresh;
+    fresh.chunks.resize(st->n_layers);
+    fresh.tokens.assign(st->n_layers, 0);
+    it = st->seqs.emplace(seq_id, std::move(fresh)).first;
+  }
+  hc_seq_state& s = it->second;
+  // generation order: a layer never holds more tokens than the layer below it
+  if (layer > 0 && s.tokens[layer - 1] < s.tokens[layer] + n_tok)
+    return fail(HC_ESTATE, "layer appended before the layer below it (layer-before-token order)");
+  // make sure the arena can take the whole append before touching anything
+  const int64_t have = (int64_t)s.chunks[layer].size() * st->chunk_tokens - s.tokens[layer];
+  const int64_t need_rows = n_tok > have ? n_tok - have : 0;
+  const int64_t need_chunks = (need_rows + st->chunk_tokens - 1) / st->chunk_tokens;
+  const int64_t avail = (int64_t)st->free_list.size() + (st->capacity_chunks - st->next_fresh);
+  if (need_chunks > avail) return fail(HC_ERANGE, "chunk arena is full");
+
+  size_t src_off = 0;
+  int32_t left = n_tok;
+  while (left > 0) {
+    const int64_t fill = s.tokens[layer] % st->chunk_tokens;
+    if (fill == 0 && s.tokens[layer] == (int64_t)s.chunks[layer].size() * st->chunk_tokens) {
+      int64_t slot;
+      if (!st->free_list.empty()) {
+        slot = st->free_list.back();
+        st->free_list.pop_back();
+      } else {
+        slot = st->next_fresh++;
+      }
+      s.chunks[layer].push_back(slot);
+    }
+    const int64_t room = st->chunk_tokens - fill;
+    const int32_t take = left < room ? left : (int32_t)room;
+    StorePiece pc;
+    pc.dst = st->arena + (size_t)s.chunks[layer].back() * st->chunk_bytes + (size_t)fill * st->row_bytes;
+    pc.src_off = src_off;
+    pc.bytes = (size_t)take * st->row_bytes;
+    pieces.push_back(pc);
+    src_off += pc.bytes;
+    s.tokens[layer] += take;
+    left -= take;
+  }
+  return HC_OK;
+}
+
+}  // namespace hc
+
+extern "C" {
+
 hc_status hc_store_append(hc_store* st, int64_t seq_id, int32_t layer, const void* h_rows,
                           int32_t n_tok) {
   clear_error();
@@ -75,64 +135,11 @@ hc_status hc_store_append(hc_store* st, int64_t seq_id, int32_t layer, const voi
   if (n_tok < 0) return fail(HC_EINVAL, "negative token count");
   if (n_tok == 0) return HC_OK;
   if (!h_rows) return fail(HC_EINVAL, "rows pointer is null");
-  // Index update under the lock (the saver's daemon threads append concurrently); the row
-  // payload is copied afterwards, outside of it.
-  struct Piece { unsigned char* dst; size_t src_off, bytes; };
-  Piece pieces_small[8];
-  std::vector<Piece> pieces_big;
-  int n_pieces = 0;
-  {
-    std::lock_guard<std::mutex> lock(st->index_mutex);
-    auto it = st->seqs.find(seq_id);
-    if (it == st->seqs.end()) {
-      hc_seq_state fresh;
-      fresh.chunks.resize(st->n_layers);
-      fresh.tokens.assign(st->n_layers, 0);
-      it = st->seqs.emplace(seq_id, std::move(fresh)).first;
-    }
-    hc_seq_state& s = it->second;
-    // generation order: a layer never holds more tokens than the layer below it
-    if (layer > 0 && s.tokens[layer - 1] < s.tokens[layer] + n_tok)
-      return fail(HC_ESTATE, "layer appended before the layer below it (layer-before-token order)");
-    // make sure the arena can take the whole append before touching anything
-    const int64_t have = (int64_t)s.chunks[layer].size() * st->chunk_tokens - s.tokens[layer];
-    const int64_t need_rows = n_tok > have ? n_tok - have : 0;
-    const int64_t need_chunks = (need_rows + st->chunk_tokens - 1) / st->chunk_tokens;
-    const int64_t avail = (int64_t)st->free_list.size() + (st->capacity_chunks - st->next_fresh);
-    if (need_chunks > avail) return fail(HC_ERANGE, "chunk arena is full");
-
-    size_t src_off = 0;
-    int32_t left = n_tok;
-    while (left > 0) {
-      const int64_t fill = s.tokens[layer] % st->chunk_tokens;
-      if (fill == 0 && s.tokens[layer] == (int64_t)s.chunks[layer].size() * st->chunk_tokens) {
-        int64_t slot;
-        if (!st->free_list.empty()) {
-          slot = st->free_list.back();
-          st->free_list.pop_back();
-        } else {
-          slot = st->next_fresh++;
-        }
-        s.chunks[layer].push_back(slot);
-      }
-      const int64_t room = st->chunk_tokens - fill;
-      const int32_t take = left < room ? left : (int32_t)room;
-      Piece pc;
-      pc.dst = st->arena + (size_t)s.chunks[layer].back() * st->chunk_bytes + (size_t)fill * st->row_bytes;
-      pc.src_off = src_off;
-      pc.bytes = (size_t)take * st->row_bytes;
-      if (n_pieces < 8) pieces_small[n_pieces] = pc; else pieces_big.push_back(pc);
-      ++n_pieces;
-      src_off += pc.bytes;
-      s.tokens[layer] += take;
-      left -= take;
-    }
-  }
+  std::vector<StorePiece> pieces;
+  hc_status r = store_reserve(st, seq_id, layer, n_tok, pieces);
+  if (r != HC_OK) return r;
   const unsigned char* src = static_cast<const unsigned char*>(h_rows);
-  for (int i = 0; i < n_pieces; ++i) {
-    const Piece& pc = i < 8 ? pieces_small[i] : pieces_big[i - 8];
-    memcpy(pc.dst, src + pc.src_off, pc.bytes);
-  }
+  for (const StorePiece& pc : pieces) memcpy(pc.dst, src + pc.src_off, pc.bytes);
   return HC_OK;
 }
 

@@ -55,22 +55,22 @@ def test_saver_matches_oracle_store(hc, n_threads, n_slots):
     store.destroy()
 
 
-def test_saver_reports_daemon_errors(hc):
+def test_saver_reports_errors(hc):
     L, d, CT = 2, 8, 4
     store = hc.Store(L, d, CT, capacity_chunks=2, pinned=False)
     saver = hc.Saver(store, 16, n_slots=2, n_threads=2)
     rows = np.zeros((12, d), dtype=np.uint16)
     seq = np.full(12, 5, dtype=np.int64)
-    saver.save_layer_host(0, rows, 12, seq)            # needs 3 chunks, the arena has 2
+    # the index half of the save runs inside the call: a full arena is reported at once
     with pytest.raises(hc.HCacheError) as e:
-        saver.flush()
+        saver.save_layer_host(0, rows, 12, seq)        # needs 3 chunks, the arena has 2
     assert e.value.status == hc.HC_ERANGE and "arena" in str(e.value)
-    saver.flush()                                      # the error is reported once
-    # layer order violation is caught by the store and surfaces at flush
-    saver.save_layer_host(1, rows[:1], 1, np.array([9], dtype=np.int64))
+    assert store.tokens(5, 0) == 0
+    # so is a layer that runs ahead of the layer below it
     with pytest.raises(hc.HCacheError) as e:
-        saver.flush()
+        saver.save_layer_host(1, rows[:1], 1, np.array([9], dtype=np.int64))
     assert e.value.status == hc.HC_ESTATE
+    saver.flush()
     # argument checks
     for args, status in [((5, rows, 1, seq), hc.HC_ERANGE), ((0, rows, 17, seq), hc.HC_ERANGE),
                          ((0, None, 1, seq), hc.HC_EINVAL), ((0, rows, -1, seq), hc.HC_EINVAL)]:
