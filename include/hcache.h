@@ -226,6 +226,26 @@ hc_status hc_saver_save_layer_host(hc_saver* saver, int32_t layer, const void* h
  * message, else HC_OK. */
 hc_status hc_saver_flush(hc_saver* saver);
 
+/* ---- bubble-free layer partition (Section 4.1.2) ---------------------------------------
+ * Given per-layer times measured offline on a platform -- io_h: transfer of one layer's
+ * hidden states, io_kv: transfer of one layer's KV cache, c_h: projection of one layer from
+ * hidden states, c_token: recomputation of one layer from tokens -- split n_layers into
+ * *l_h layers restored from hidden states and *l_o layers restored by the complementary
+ * method so that transfer and compute finish together:
+ *   c_h >  io_h (compute-bound): complement = KV offload (*complement = HC_COMPLEMENT_KV),
+ *       l_h = ceil(n * io_kv / (io_kv + c_h - io_h));
+ *   c_h <= io_h (transfer-bound): complement = token recomputation (HC_COMPLEMENT_RECOMPUTE),
+ *       l_h = ceil(n * c_token / (c_token + io_h - c_h));
+ *   l_o = n - l_h.  Pure host arithmetic; times in any common unit, all > 0.  The closed forms
+ * rest on the method's premises io_kv > io_h and c_token > c_h (hidden states are the smaller
+ * transfer and the cheaper compute); inputs that break them -- e.g. a grouped-query model whose
+ * KV cache is narrower than its hidden states -- return HC_EINVAL, since one of the plain
+ * methods alone is then at least as fast.
+ * This library restores the l_h share; the complements belong to the serving engine. */
+enum { HC_COMPLEMENT_KV = 0, HC_COMPLEMENT_RECOMPUTE = 1 };
+hc_status hc_partition_layers(int32_t n_layers, double io_h, double io_kv, double c_h,
+                              double c_token, int32_t* l_h, int32_t* l_o, int32_t* complement);
+
 /* Loader used by hc_restore_context: 0 (default) = copy engines: chunks of a layer whose
  * arena slots are equally spaced (the usual result of saving in generation order) move in
  * ONE strided copy, irregular placements in one copy per run; the compute units stay free

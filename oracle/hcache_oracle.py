@@ -236,6 +236,34 @@ def save_step(store, layer, rows, row_seq):
         store.append(int(s), layer, r[None, :])
 
 
+# ------------------------------------------------------------ bubble-free partition
+def restoration_time(l_h, n_layers, io_h, io_kv, c_h, c_token):
+    """Pipelined restoration time when l_h layers come from hidden states and the rest from
+    the complementary method (Section 4.1.2).  Compute-bound platform (c_h > io_h): the
+    complement is KV offload, which only adds transfer: max(c_h*l_h, io_h*l_h + io_kv*l_o),
+    the paper's min-max objective.  Transfer-bound platform: the complement is token
+    recomputation, which only adds compute: max(c_h*l_h + c_token*l_o, io_h*l_h)."""
+    l_o = n_layers - l_h
+    if c_h > io_h:
+        return max(c_h * l_h, io_h * l_h + io_kv * l_o)
+    return max(c_h * l_h + c_token * l_o, io_h * l_h)
+
+
+def partition_layers(n_layers, io_h, io_kv, c_h, c_token):
+    """The closed forms of Section 4.1.2: (l_h, l_o, complement), complement 'kv' or 're'.
+    Premises of the method: io_kv > io_h and c_token > c_h."""
+    import math
+    assert io_kv > io_h and c_token > c_h
+    if c_h > io_h:
+        l_h = math.ceil(n_layers * io_kv / (io_kv + c_h - io_h) - 1e-9 * n_layers)
+        comp = "kv"
+    else:
+        l_h = math.ceil(n_layers * c_token / (c_token + io_h - c_h) - 1e-9 * n_layers)
+        comp = "re"
+    l_h = min(max(l_h, 0), n_layers)
+    return l_h, n_layers - l_h, comp
+
+
 # --------------------------------------------------------------- cost accounting
 def restore_flop(n_tokens, d_model, d_kv):
     """Floating-point operations of one layer's projection, one multiply-add = 2

@@ -67,6 +67,8 @@ def _load():
         "hc_store_drop": (i32, [vp, i64]),
         "hc_restore_context": (i32, [vp, vp, i64, i32, i32, i32, vp, i32, vp, vp]),
         "hc_set_loader": (i32, [vp, i32]),
+        "hc_partition_layers": (i32, [i32, C.c_double, C.c_double, C.c_double, C.c_double,
+                                      p(i32), p(i32), p(i32)]),
         "hc_saver_create": (i32, [vp, i32, i32, i32, p(vp)]),
         "hc_saver_destroy": (i32, [vp]),
         "hc_saver_save_layer": (i32, [vp, i32, vp, i32, vp, vp, vp]),
@@ -87,7 +89,7 @@ EXPORTED = ("hc_last_error hc_version hc_validate_desc hc_create hc_destroy hc_s
             "hc_store_create_ex hc_store_destroy hc_store_append hc_store_tokens hc_store_chunk "
             "hc_store_drop hc_restore_context hc_set_loader hc_timing_begin hc_timing_end "
             "hc_saver_create hc_saver_destroy hc_saver_save_layer hc_saver_save_layer_host "
-            "hc_saver_flush").split()
+            "hc_saver_flush hc_partition_layers").split()
 
 
 def _check(status):
@@ -101,6 +103,15 @@ def version():
 
 def validate_desc(desc):
     _check(lib.hc_validate_desc(C.byref(desc)))
+
+
+def partition_layers(n_layers, io_h, io_kv, c_h, c_token):
+    """(l_h, l_o, complement) of the bubble-free layer partition; complement 0 = KV offload,
+    1 = token recomputation."""
+    lh, lo, comp = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+    _check(lib.hc_partition_layers(n_layers, io_h, io_kv, c_h, c_token, C.byref(lh), C.byref(lo),
+                                   C.byref(comp)))
+    return lh.value, lo.value, comp.value
 
 
 def _ptr(x):

@@ -250,6 +250,35 @@ hc_status hc_poll_device_error(hc_ctx* ctx, void* stream, int32_t* out_flags) {
   return HC_OK;
 }
 
+hc_status hc_partition_layers(int32_t n_layers, double io_h, double io_kv, double c_h,
+                              double c_token, int32_t* l_h, int32_t* l_o, int32_t* complement) {
+  clear_error();
+  if (!l_h || !l_o || !complement) return fail(HC_EINVAL, "null output pointer");
+  if (n_layers <= 0) return fail(HC_EINVAL, "n_layers must be positive");
+  if (!(io_h > 0) || !(io_kv > 0) || !(c_h > 0) || !(c_token > 0))
+    return fail(HC_EINVAL, "times must be positive");
+  if (!(io_kv > io_h))
+    return fail(HC_EINVAL, "io_kv <= io_h: KV offload alone moves no more data than hidden states");
+  if (!(c_token > c_h))
+    return fail(HC_EINVAL, "c_token <= c_h: recomputation alone is no slower than projection");
+  double x;
+  if (c_h > io_h) {
+    *complement = HC_COMPLEMENT_KV;
+    x = n_layers * io_kv / (io_kv + c_h - io_h);
+  } else {
+    *complement = HC_COMPLEMENT_RECOMPUTE;
+    x = n_layers * c_token / (c_token + io_h - c_h);
+  }
+  // ceil with a guard against a quotient that lands a few ulps above an integer
+  int32_t lh = (int32_t)x;
+  if ((double)lh < x - 1e-9 * (double)n_layers) ++lh;
+  if (lh > n_layers) lh = n_layers;
+  if (lh < 0) lh = 0;
+  *l_h = lh;
+  *l_o = n_layers - lh;
+  return HC_OK;
+}
+
 hc_status hc_set_loader(hc_ctx* ctx, int32_t mode) {
   clear_error();
   if (!ctx) return fail(HC_EINVAL, "ctx is null");

@@ -402,6 +402,40 @@ def check_save_step(o):
     assert st.n_chunks(10, 0) == 2 and st.chunk(10, 0, 1).shape == (1, 2)
 
 
+def check_partition(o):
+    """The closed forms of Section 4.1.2 against the optimisation problem they claim to solve
+    (brute force over every split) and against the schedules of Table 3."""
+    rng = np.random.default_rng(2)
+    for _ in range(300):
+        n = int(rng.integers(1, 97))
+        io_h = float(rng.uniform(0.2, 3.0))
+        c_h = float(rng.uniform(0.2, 3.0))
+        io_kv = 2.0 * io_h if rng.random() < 0.5 else io_h * float(rng.uniform(1.05, 4.0))
+        c_tok = c_h * float(rng.uniform(1.05, 12.0))
+        l_h, l_o, comp = o.partition_layers(n, io_h, io_kv, c_h, c_tok)
+        assert l_h + l_o == n and 0 <= l_h <= n
+        assert comp == ("kv" if c_h > io_h else "re")
+        times = [o.restoration_time(k, n, io_h, io_kv, c_h, c_tok) for k in range(n + 1)]
+        best = int(np.argmin(times))
+        # the formula rounds the continuous balance point up: it is the integer optimum or one above
+        assert l_h in (best, best + 1), (n, io_h, io_kv, c_h, c_tok, l_h, best)
+        # and costs at most one layer's worth of the binding resource over the optimum
+        assert times[l_h] <= min(times) + max(c_h, io_h) + 1e-9
+    # the objective is the paper's: with everything from hidden states it is max(C_H, IO_H) * N
+    assert o.restoration_time(32, 32, 1.0, 2.0, 1.5, 9.0) == 48.0
+    assert o.restoration_time(0, 32, 1.0, 2.0, 1.5, 9.0) == 64.0          # pure KV offload: IO_KV * N
+    # Table 3 (KV cache = 2x hidden bytes under MHA, so IO_KV = 2 IO_H):
+    #   Llama2-7B  "31 H + 1 KV": any C_H / IO_H in [1.065, 1.133) gives 31 of 32 layers
+    #   Llama2-13B "36 H + 4 KV": any ratio in [1.2223, 1.2857) gives 36 of 40
+    for n, want, ratios in ((32, 31, (1.07, 1.10, 1.13)), (40, 36, (1.23, 1.25, 1.28))):
+        for r in ratios:
+            assert o.partition_layers(n, 1.0, 2.0, r, 10.0) == (want, n - want, "kv"), (n, r)
+    #   OPT-30B "40 H + 8 RE" (transfer-bound): 48 C_T / (C_T + IO_H - C_H) in (39, 40]
+    assert o.partition_layers(48, 1.0, 2.0, 0.5, 2.4) == (40, 8, "re")   # 48*2.4/2.9 = 39.7
+    # balanced platform: everything from hidden states
+    assert o.partition_layers(32, 1.0, 2.0, 1.0, 9.0) == (32, 0, "re")
+
+
 # --------------------------------------------------------------- cost accounting
 def check_cost_accounting(o):
     g = golden_constants()
@@ -432,5 +466,6 @@ ALL_CHECKS = (
     check_ragged,
     check_store,
     check_save_step,
+    check_partition,
     check_cost_accounting,
 )

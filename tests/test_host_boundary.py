@@ -136,3 +136,22 @@ def test_create_fails_loudly_without_gpu(hc):
     with pytest.raises(hc.HCacheError) as e:
         hc.Context(good_desc(hc))
     assert e.value.status == hc.HC_EHIP
+
+
+def test_partition_matches_oracle(hc):
+    """The library's closed-form layer partition against the oracle (which is itself pinned to
+    the brute-force optimum and to the schedules the paper prints)."""
+    rng = np.random.default_rng(8)
+    for _ in range(500):
+        n = int(rng.integers(1, 129))
+        io_h, c_h = float(rng.uniform(0.1, 3)), float(rng.uniform(0.1, 3))
+        io_kv, c_tok = io_h * float(rng.uniform(1.01, 6)), c_h * float(rng.uniform(1.01, 20))
+        l_h, l_o, comp = hc.partition_layers(n, io_h, io_kv, c_h, c_tok)
+        want = oracle.partition_layers(n, io_h, io_kv, c_h, c_tok)
+        assert (l_h, l_o, "kv" if comp == 0 else "re") == want
+    assert hc.partition_layers(32, 1.0, 2.0, 1.1, 10.0) == (31, 1, 0)
+    for bad in [(0, 1, 1, 1, 1), (4, 0, 1, 1, 1), (4, 1, -1, 1, 1), (4, 1, 1, 0, 1), (4, 1, 1, 1, float("nan")),
+                (4, 2, 1, 3, 9), (4, 1, 2, 3, 2)]:
+        with pytest.raises(hc.HCacheError) as e:
+            hc.partition_layers(*bad)
+        assert e.value.status == hc.HC_EINVAL

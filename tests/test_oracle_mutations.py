@@ -135,6 +135,22 @@ def mut_save_rows_to_wrong_context(o):
     o.save_step = lambda store, layer, rows, row_seq: real(store, layer, rows, list(row_seq)[::-1])
 
 
+def mut_partition_floor(o):
+    real = o.partition_layers
+
+    def partition_layers(n, io_h, io_kv, c_h, c_token):
+        l_h, l_o, comp = real(n, io_h, io_kv, c_h, c_token)
+        x = n * io_kv / (io_kv + c_h - io_h) if c_h > io_h else n * c_token / (c_token + io_h - c_h)
+        l_h = min(int(x), n)
+        return l_h, n - l_h, comp
+    o.partition_layers = partition_layers
+
+
+def mut_partition_wrong_branch(o):
+    real = o.partition_layers
+    o.partition_layers = lambda n, io_h, io_kv, c_h, c_token: real(n, c_h, io_kv, io_h, c_token)
+
+
 def mut_flop_count(o):
     o.restore_flop = lambda n, d, dkv: 2 * n * d * dkv
 
