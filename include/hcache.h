@@ -178,14 +178,47 @@ hc_status hc_store_drop(hc_store* store, int64_t seq_id);
  * staging buffers on `copy_stream` -- by the copy engines, one (strided) hipMemcpy2DAsync /
  * hipMemcpyAsync per run of equally spaced chunks, or by a gather kernel that reads the
  * pinned arena over the host link (hc_set_loader) -- and the restoration kernel runs on
- * `compute_stream`;
- * events order the two so that the transfer of layer L+1 overlaps the kernel of layer L.  Staging buffers are allocated inside the call when the
- * context has none large enough.  Returns after everything is enqueued; the caller
- * synchronises `compute_stream`.  The two streams must differ. */
+ * `compute_stream`; events order the two so that the transfer of layer L+1 overlaps the
+ * kernel of layer L.  Staging buffers are allocated inside the call when the context has
+ * none large enough.  Returns after everything is enqueued; the caller synchronises
+ * `compute_stream`.  The two streams must differ. */
 hc_status hc_restore_context(hc_ctx* ctx, const hc_store* store, int64_t seq_id,
                              int32_t tok_begin, int32_t n_tok, int32_t pos_offset,
                              const int32_t* d_block_table, int32_t n_blocks,
                              void* compute_stream, void* copy_stream);
+
+/* ---- KV-offload complement (Section 4.1.2; Figure "Two ways to combine ... with KV
+ * offload", layer-wise partition) ---------------------------------------------------------
+ * Layers that the partition assigns to KV offload keep their KV cache on the host as token
+ * rows: bf16 [n_tok][K row | V row], 2 * d_kv wide, K as it sits in the cache (rotated).
+ * A KV-row store is an ordinary hc_store created with d_model = 2 * d_kv and as many layers
+ * as are offloaded.
+ *
+ * hc_gather_kv reads the rows of the given positions out of layer `layer`'s pool into
+ * d_rows (device, 16-byte aligned, n_tok * 2 * d_kv bf16): the saving direction.
+ * hc_scatter_kv writes such rows into the pages the block table names: the restoring
+ * direction.  Both are byte copies (bit-exact), asynchronous on `stream`; invalid rows are
+ * skipped and flagged exactly as in hc_restore_kv. */
+hc_status hc_gather_kv(hc_ctx* ctx, int32_t layer, void* d_rows, const int32_t* d_positions,
+                       int32_t n_tok, const int32_t* d_block_table, int32_t n_blocks,
+                       void* stream);
+hc_status hc_scatter_kv(hc_ctx* ctx, int32_t layer, const void* d_rows,
+                        const int32_t* d_positions, int32_t n_tok, const int32_t* d_block_table,
+                        int32_t n_blocks, void* stream);
+
+/* hc_restore_context with a layer-wise partition: layers [0, l_h) are restored from
+ * `hidden_store` (at least l_h layers, rows d_model wide; may be NULL when l_h = 0) by the
+ * restoration kernel, layers [l_h, n_layers) from `kv_store` (exactly n_layers - l_h layers,
+ * rows 2 * d_kv wide, its layer j = model layer l_h + j; may be NULL when l_h = n_layers) by
+ * a row-to-page copy.  Transfers run in layer order on `copy_stream`, so the hidden states
+ * stream first and the offloaded KV fills the time the link would otherwise idle while the
+ * projections finish.  Needs weights only for the first l_h layers.  Everything else as
+ * hc_restore_context. */
+hc_status hc_restore_context_mixed(hc_ctx* ctx, const hc_store* hidden_store,
+                                   const hc_store* kv_store, int32_t l_h, int64_t seq_id,
+                                   int32_t tok_begin, int32_t n_tok, int32_t pos_offset,
+                                   const int32_t* d_block_table, int32_t n_blocks,
+                                   void* compute_stream, void* copy_stream);
 
 /* ---- two-stage saving of new hidden states (Section 4.2.2; Section 5 "Pipelined state
  * transmission", "Storage management") -------------------------------------------------
@@ -241,7 +274,8 @@ hc_status hc_saver_flush(hc_saver* saver);
  * transfer and the cheaper compute); inputs that break them -- e.g. a grouped-query model whose
  * KV cache is narrower than its hidden states -- return HC_EINVAL, since one of the plain
  * methods alone is then at least as fast.
- * This library restores the l_h share; the complements belong to the serving engine. */
+ * This library restores the l_h share and the KV-offload complement (hc_restore_context_mixed);
+ * token recomputation is a full forward pass and belongs to the serving engine. */
 enum { HC_COMPLEMENT_KV = 0, HC_COMPLEMENT_RECOMPUTE = 1 };
 hc_status hc_partition_layers(int32_t n_layers, double io_h, double io_kv, double c_h,
                               double c_token, int32_t* l_h, int32_t* l_o, int32_t* complement);

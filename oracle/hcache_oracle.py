@@ -142,6 +142,16 @@ def gather_kv(pool, positions, block_table, block_size):
     return pool[page, 0, slot], pool[page, 1, slot]
 
 
+def scatter_kv(pool, k, v, positions, block_table, block_size):
+    """KV-offload restoration of one layer (Section 4.1.2, layer-wise partition): the saved
+    K and V rows [T, H, hd] of the given positions go back into the pages the block table
+    names.  No arithmetic: the values are the cache's own."""
+    page, slot = page_slots(positions, block_table, block_size)
+    for t in range(len(page)):
+        pool[page[t], 0, slot[t]] = k[t]
+        pool[page[t], 1, slot[t]] = v[t]
+
+
 # -------------------------------------------------------------- full forward pass
 def full_prefill(h0, layers, positions, *, eps, theta, n_q_heads, n_kv_heads,
                  head_dim, rope_style=0):

@@ -66,6 +66,9 @@ def _load():
         "hc_store_chunk": (i32, [vp, i64, i32, i32, p(vp), p(i32)]),
         "hc_store_drop": (i32, [vp, i64]),
         "hc_restore_context": (i32, [vp, vp, i64, i32, i32, i32, vp, i32, vp, vp]),
+        "hc_gather_kv": (i32, [vp, i32, vp, vp, i32, vp, i32, vp]),
+        "hc_scatter_kv": (i32, [vp, i32, vp, vp, i32, vp, i32, vp]),
+        "hc_restore_context_mixed": (i32, [vp, vp, vp, i32, i64, i32, i32, i32, vp, i32, vp, vp]),
         "hc_set_loader": (i32, [vp, i32]),
         "hc_partition_layers": (i32, [i32, C.c_double, C.c_double, C.c_double, C.c_double,
                                       p(i32), p(i32), p(i32)]),
@@ -89,7 +92,8 @@ EXPORTED = ("hc_last_error hc_version hc_validate_desc hc_create hc_destroy hc_s
             "hc_store_create_ex hc_store_destroy hc_store_append hc_store_tokens hc_store_chunk "
             "hc_store_drop hc_restore_context hc_set_loader hc_timing_begin hc_timing_end "
             "hc_saver_create hc_saver_destroy hc_saver_save_layer hc_saver_save_layer_host "
-            "hc_saver_flush hc_partition_layers").split()
+            "hc_saver_flush hc_partition_layers hc_gather_kv hc_scatter_kv "
+            "hc_restore_context_mixed").split()
 
 
 def _check(status):
@@ -170,6 +174,21 @@ class Context:
                         compute_stream, copy_stream):
         _check(lib.hc_restore_context(self._h, store._h, seq_id, tok_begin, n_tok, pos_offset,
                                       _ptr(d_block_table), n_blocks, compute_stream, copy_stream))
+
+    def restore_context_mixed(self, hidden_store, kv_store, l_h, seq_id, tok_begin, n_tok,
+                              pos_offset, d_block_table, n_blocks, compute_stream, copy_stream):
+        _check(lib.hc_restore_context_mixed(
+            self._h, hidden_store._h if hidden_store is not None else None,
+            kv_store._h if kv_store is not None else None, l_h, seq_id, tok_begin, n_tok,
+            pos_offset, _ptr(d_block_table), n_blocks, compute_stream, copy_stream))
+
+    def gather_kv(self, layer, d_rows, d_positions, n_tok, d_block_table, n_blocks, stream=0):
+        _check(lib.hc_gather_kv(self._h, layer, _ptr(d_rows), _ptr(d_positions), n_tok,
+                                _ptr(d_block_table), n_blocks, stream))
+
+    def scatter_kv(self, layer, d_rows, d_positions, n_tok, d_block_table, n_blocks, stream=0):
+        _check(lib.hc_scatter_kv(self._h, layer, _ptr(d_rows), _ptr(d_positions), n_tok,
+                                 _ptr(d_block_table), n_blocks, stream))
 
     def set_loader(self, mode):
         _check(lib.hc_set_loader(self._h, mode))

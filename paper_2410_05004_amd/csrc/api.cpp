@@ -100,6 +100,28 @@ hc_status restore_layer(hc_ctx* ctx, int32_t layer, const void* d_hidden,
   return HC_OK;
 }
 
+hc_status kv_rows_layer(hc_ctx* ctx, int32_t layer, void* d_rows, const int32_t* d_positions,
+                        int32_t pos_base, int32_t n_tok, const int32_t* d_block_table,
+                        int32_t n_blocks, bool to_pool, hipStream_t stream) {
+  const hc_layer_state& L = ctx->layers[layer];
+  if (!L.pool) return fail(HC_ESTATE, "hc_set_kv_pool was not called for this layer");
+  KvRowsArgs a;
+  a.rows = static_cast<uint16_t*>(d_rows);
+  a.pool = L.pool;
+  a.positions = d_positions;
+  a.block_table = d_block_table;
+  a.err = ctx->err_dev;
+  a.num_pages = L.num_pages;
+  a.pos_base = pos_base;
+  a.n_tok = n_tok;
+  a.n_blocks = n_blocks;
+  a.max_position = ctx->desc.max_position;
+  a.d_kv = ctx->d_kv;
+  a.block_shift = ctx->block_shift;
+  HC_HIP(launch_kv_rows(a, to_pool, stream));
+  return HC_OK;
+}
+
 }  // namespace hc
 
 using namespace hc;
@@ -238,6 +260,35 @@ hc_status hc_restore_kv_ragged(hc_ctx* ctx, int32_t layer, const void* d_hidden,
   if (!aligned16(d_hidden)) return fail(HC_EALIGN, "hidden not 16-byte aligned");
   return restore_layer(ctx, layer, d_hidden, d_positions, 0, h_total_tokens, d_cu_seqlens, n_seq,
                        d_block_tables, max_blocks, static_cast<hipStream_t>(stream));
+}
+
+static hc_status kv_rows_entry(hc_ctx* ctx, int32_t layer, void* d_rows,
+                               const int32_t* d_positions, int32_t n_tok,
+                               const int32_t* d_block_table, int32_t n_blocks, bool to_pool,
+                               void* stream) {
+  clear_error();
+  hc_status s = check_layer(ctx, layer);
+  if (s != HC_OK) return s;
+  if (n_tok < 0 || n_blocks < 0) return fail(HC_EINVAL, "negative size");
+  if (n_tok == 0) return HC_OK;
+  if (!d_rows || !d_positions || !d_block_table) return fail(HC_EINVAL, "null device pointer");
+  if (!aligned16(d_rows)) return fail(HC_EALIGN, "rows not 16-byte aligned");
+  return kv_rows_layer(ctx, layer, d_rows, d_positions, 0, n_tok, d_block_table, n_blocks, to_pool,
+                       static_cast<hipStream_t>(stream));
+}
+
+hc_status hc_gather_kv(hc_ctx* ctx, int32_t layer, void* d_rows, const int32_t* d_positions,
+                       int32_t n_tok, const int32_t* d_block_table, int32_t n_blocks,
+                       void* stream) {
+  return kv_rows_entry(ctx, layer, d_rows, d_positions, n_tok, d_block_table, n_blocks, false,
+                       stream);
+}
+
+hc_status hc_scatter_kv(hc_ctx* ctx, int32_t layer, const void* d_rows,
+                        const int32_t* d_positions, int32_t n_tok, const int32_t* d_block_table,
+                        int32_t n_blocks, void* stream) {
+  return kv_rows_entry(ctx, layer, const_cast<void*>(d_rows), d_positions, n_tok, d_block_table,
+                       n_blocks, true, stream);
 }
 
 hc_status hc_poll_device_error(hc_ctx* ctx, void* stream, int32_t* out_flags) {

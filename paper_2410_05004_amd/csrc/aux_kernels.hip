@@ -134,4 +134,53 @@ hipError_t launch_gather(const CopySegment* segs, int n_seg, hipStream_t stream)
   return hipGetLastError();
 }
 
+// ---- KV rows <-> paged pool --------------------------------------------------------------
+// The KV-offload complement of the bubble-free scheduler (paper Section 4.1.2): layers that
+// are not restored from hidden states keep their KV cache on the host as token rows
+// [n_tok][K row | V row] (2 * d_kv bf16, K already rotated).  TO_POOL copies such rows into
+// the pages the block table names (restoration); otherwise pages are read out into rows
+// (saving).  Pure byte movement, one 16-byte word per lane; a row with an invalid position
+// or page is skipped and raises the same sticky flags as the fused kernel.
+template <bool TO_POOL>
+__global__ __launch_bounds__(256) void kv_rows_kernel(KvRowsArgs a) {
+  const int vec_per_part = a.d_kv >> 3;                // 16-byte words per K (or V) row
+  const int vec_per_row = 2 * vec_per_part;
+  const long total = (long)a.n_tok * vec_per_row;
+  for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+    const int t = (int)(i / vec_per_row);
+    const int j = (int)(i - (long)t * vec_per_row);
+    const int part = j >= vec_per_part;                // 0 = K, 1 = V
+    const int jj = j - part * vec_per_part;
+    const int pos = a.positions ? a.positions[t] : a.pos_base + t;
+    if (pos < 0 || pos >= a.max_position || (pos >> a.block_shift) >= a.n_blocks) {
+      if (j == 0) atomicOr(a.err, HC_DEV_BAD_POSITION);
+      continue;
+    }
+    const long page = a.block_table[pos >> a.block_shift];
+    if (page < 0 || page >= a.num_pages) {
+      if (j == 0) atomicOr(a.err, HC_DEV_BAD_PAGE);
+      continue;
+    }
+    const int slot = pos & ((1 << a.block_shift) - 1);
+    const long rows_per_page = 2L << a.block_shift;
+    gather_vec* in_pool = reinterpret_cast<gather_vec*>(a.pool) +
+        ((page * rows_per_page + ((long)part << a.block_shift) + slot) * vec_per_part + jj);
+    gather_vec* in_rows = reinterpret_cast<gather_vec*>(a.rows) + i;
+    if (TO_POOL) *in_pool = __builtin_nontemporal_load(in_rows);
+    else *in_rows = *in_pool;
+  }
+}
+
+hipError_t launch_kv_rows(const KvRowsArgs& a, bool to_pool, hipStream_t stream) {
+  if (a.n_tok <= 0) return hipSuccess;
+  const long total = (long)a.n_tok * (a.d_kv >> 2);
+  long blocks = (total + 255) / 256;
+  if (blocks > 256 * 16) blocks = 256 * 16;
+  if (to_pool)
+    hipLaunchKernelGGL(kv_rows_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+  else
+    hipLaunchKernelGGL(kv_rows_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
 }  // namespace hc

@@ -80,6 +80,18 @@ constexpr int kGatherBlocksPerSegment = 8;
 // (kGatherBlocksPerSegment workgroups per segment); `segs` must be device-readable.
 hipError_t launch_gather(const CopySegment* segs, int n_seg, hipStream_t stream);
 
+// Token rows [n_tok][K | V] (2 * d_kv bf16) <-> pages of one layer's pool.
+struct KvRowsArgs {
+  uint16_t* rows;                // bf16 [n_tok][2 * d_kv]
+  uint16_t* pool;                // bf16 [num_pages][2][block_size][d_kv]
+  const int32_t* positions;      // [n_tok] or nullptr: position = pos_base + row
+  const int32_t* block_table;    // [n_blocks]
+  int32_t* err;                  // sticky error word
+  int64_t num_pages;
+  int32_t pos_base, n_tok, n_blocks, max_position, d_kv, block_shift;
+};
+hipError_t launch_kv_rows(const KvRowsArgs& a, bool to_pool, hipStream_t stream);
+
 // Error plumbing: thread-local message + status.
 hc_status fail(hc_status code, const std::string& msg);
 hc_status fail_hip(hipError_t e, const char* what);
@@ -101,6 +113,10 @@ hc_status restore_layer(hc_ctx* ctx, int32_t layer, const void* d_hidden,
                         const int32_t* d_positions, int32_t pos_base, int32_t n_tok,
                         const int32_t* d_cu, int32_t n_seq, const int32_t* d_tables,
                         int32_t max_blocks, hipStream_t stream);
+// Validated launch of the KV row copy for one layer: rows -> pages (to_pool) or pages -> rows.
+hc_status kv_rows_layer(hc_ctx* ctx, int32_t layer, void* d_rows, const int32_t* d_positions,
+                        int32_t pos_base, int32_t n_tok, const int32_t* d_block_table,
+                        int32_t n_blocks, bool to_pool, hipStream_t stream);
 }  // namespace hc
 
 struct hc_layer_state {
@@ -119,7 +135,7 @@ struct hc_ctx {
   std::vector<hc_layer_state> layers;
   // staging for hc_restore_context
   uint16_t* stage[2] = {nullptr, nullptr};
-  int64_t stage_tokens = 0;
+  size_t stage_bytes = 0;
   hipEvent_t h2d_done[2] = {nullptr, nullptr};
   hipEvent_t buf_free[2] = {nullptr, nullptr};
   int loader_mode = 0;                    // 0 = copy engines (strided runs), 1 = gather kernel

@@ -177,25 +177,38 @@ hc_status hc_store_drop(hc_store* st, int64_t seq_id) {
   return HC_OK;
 }
 
-hc_status hc_restore_context(hc_ctx* ctx, const hc_store* st, int64_t seq_id, int32_t tok_begin,
-                             int32_t n_tok, int32_t pos_offset, const int32_t* d_block_table,
-                             int32_t n_blocks, void* compute_stream, void* copy_stream) {
-  clear_error();
-  if (!ctx || !st) return fail(HC_EINVAL, "null ctx or store");
-  if (st->n_layers != ctx->desc.n_layers || st->d_model != ctx->desc.d_model)
-    return fail(HC_EINVAL, "store and context disagree on n_layers / d_model");
+// Shared body of the whole-context restores.  Layers [0, l_h) come from the hidden-state
+// store `hs` through the fused kernel; layers [l_h, n_layers) come from the KV-row store `ks`
+// (layer index l - l_h there) through the row-to-page copy.  Both kinds go through the same
+// two staging buffers and the same event handshake, in layer order, so the hidden states
+// stream without a gap and the offloaded KV follows them (paper Section 4.1.2).
+static hc_status restore_context_impl(hc_ctx* ctx, const hc_store* hs, const hc_store* ks,
+                                      int32_t l_h, int64_t seq_id, int32_t tok_begin,
+                                      int32_t n_tok, int32_t pos_offset,
+                                      const int32_t* d_block_table, int32_t n_blocks,
+                                      void* compute_stream, void* copy_stream) {
+  const int L = ctx->desc.n_layers;
   if (tok_begin < 0 || n_tok < 0 || n_blocks < 0) return fail(HC_EINVAL, "negative size");
   if (n_tok == 0) return HC_OK;
   if (!d_block_table) return fail(HC_EINVAL, "block table is null");
   if (compute_stream == copy_stream) return fail(HC_EINVAL, "compute and copy streams must differ");
-  auto it = st->seqs.find(seq_id);
-  if (it == st->seqs.end()) return fail(HC_ERANGE, "unknown context");
-  const hc_seq_state& s = it->second;
-  const int L = ctx->desc.n_layers;
+  const hc_seq_state* hseq = nullptr;
+  const hc_seq_state* kseq = nullptr;
+  if (l_h > 0) {
+    auto it = hs->seqs.find(seq_id);
+    if (it == hs->seqs.end()) return fail(HC_ERANGE, "unknown context");
+    hseq = &it->second;
+  }
+  if (l_h < L) {
+    auto it = ks->seqs.find(seq_id);
+    if (it == ks->seqs.end()) return fail(HC_ERANGE, "unknown context in the KV store");
+    kseq = &it->second;
+  }
   for (int l = 0; l < L; ++l) {
-    if (s.tokens[l] < (int64_t)tok_begin + n_tok)
+    const int64_t have = l < l_h ? hseq->tokens[l] : kseq->tokens[l - l_h];
+    if (have < (int64_t)tok_begin + n_tok)
       return fail(HC_ERANGE, "token range exceeds what the store holds for some layer");
-    if (!ctx->layers[l].wpack || !ctx->layers[l].pool)
+    if ((l < l_h && !ctx->layers[l].wpack) || !ctx->layers[l].pool)
       return fail(HC_ESTATE, "weights or KV pool missing for some layer");
   }
   if ((int64_t)pos_offset + tok_begin + n_tok > ctx->desc.max_position || pos_offset < 0)
@@ -204,20 +217,23 @@ hc_status hc_restore_context(hc_ctx* ctx, const hc_store* st, int64_t seq_id, in
   hipStream_t xs = static_cast<hipStream_t>(copy_stream);
 
   // staging buffers and events
-  if (ctx->stage_tokens < n_tok) {
+  size_t need_bytes = 0;
+  if (l_h > 0) need_bytes = (size_t)n_tok * hs->row_bytes;
+  if (l_h < L && (size_t)n_tok * ks->row_bytes > need_bytes) need_bytes = (size_t)n_tok * ks->row_bytes;
+  if (ctx->stage_bytes < need_bytes) {
     for (int b = 0; b < 2; ++b) {
       if (ctx->stage[b]) { HC_HIP(hipFree(ctx->stage[b])); ctx->stage[b] = nullptr; }
     }
-    ctx->stage_tokens = 0;
+    ctx->stage_bytes = 0;
     for (int b = 0; b < 2; ++b) {
-      hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->stage[b]), (size_t)n_tok * st->row_bytes);
+      hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->stage[b]), need_bytes);
       if (e != hipSuccess) {
         (void)hipGetLastError();
         ctx->stage[b] = nullptr;
         return fail(HC_ENOMEM, "device allocation of a staging buffer failed");
       }
     }
-    ctx->stage_tokens = n_tok;
+    ctx->stage_bytes = need_bytes;
   }
   for (int b = 0; b < 2; ++b) {
     if (!ctx->h2d_done[b]) HC_HIP(hipEventCreateWithFlags(&ctx->h2d_done[b], hipEventDisableTiming));
@@ -230,15 +246,15 @@ hc_status hc_restore_context(hc_ctx* ctx, const hc_store* st, int64_t seq_id, in
   // Segments: one per run of equally spaced chunks of a layer.  Chunks that arrive in
   // generation order are spaced n_layers slots apart (or adjacent after a long prefill), so a
   // whole layer is usually a single run: one strided copy.
-  const int CT = st->chunk_tokens;
-  const int c_first = tok_begin / CT, c_last = (tok_begin + n_tok - 1) / CT;
   struct Run { const unsigned char* src; unsigned char* dst; size_t row_bytes; size_t pitch; int rows; };
   std::vector<Run> runs;
   std::vector<CopySegment> segs;                        // host scratch
-  auto stage_at = [&](int b, int c, int lo) {
-    return reinterpret_cast<unsigned char*>(ctx->stage[b]) + (size_t)(c * CT + lo - tok_begin) * st->row_bytes;
-  };
-  auto build = [&](int l, int b) {
+  auto build = [&](const hc_store* st, const hc_seq_state& s, int l, int b) {
+    const int CT = st->chunk_tokens;
+    const int c_first = tok_begin / CT, c_last = (tok_begin + n_tok - 1) / CT;
+    auto stage_at = [&](int c, int lo) {
+      return reinterpret_cast<unsigned char*>(ctx->stage[b]) + (size_t)(c * CT + lo - tok_begin) * st->row_bytes;
+    };
     runs.clear();
     segs.clear();
     for (int c = c_first; c <= c_last; ++c) {           // one segment per chunk (gather kernel)
@@ -246,7 +262,7 @@ hc_status hc_restore_context(hc_ctx* ctx, const hc_store* st, int64_t seq_id, in
       const int hi = c == c_last ? tok_begin + n_tok - c * CT : CT;
       CopySegment g;
       g.src = st->arena + (size_t)s.chunks[l][c] * st->chunk_bytes + (size_t)lo * st->row_bytes;
-      g.dst = stage_at(b, c, lo);
+      g.dst = stage_at(c, lo);
       g.bytes = (size_t)(hi - lo) * st->row_bytes;
       segs.push_back(g);
     }
@@ -258,7 +274,7 @@ hc_status hc_restore_context(hc_ctx* ctx, const hc_store* st, int64_t seq_id, in
       const int hi = c == c_last ? tok_begin + n_tok - c * CT : CT;
       const unsigned char* src = st->arena + (size_t)s.chunks[l][c] * st->chunk_bytes + (size_t)lo * st->row_bytes;
       if (lo != 0 || hi != CT) {
-        runs.push_back({src, stage_at(b, c, lo), (size_t)(hi - lo) * st->row_bytes, 0, 1});
+        runs.push_back({src, stage_at(c, lo), (size_t)(hi - lo) * st->row_bytes, 0, 1});
         ++c;
         continue;
       }
@@ -273,21 +289,23 @@ hc_status hc_restore_context(hc_ctx* ctx, const hc_store* st, int64_t seq_id, in
                  s.chunks[l][c_end + 1] - s.chunks[l][c_end] == stride) ++c_end;
         }
       }
-      runs.push_back({src, stage_at(b, c, 0), st->chunk_bytes, (size_t)stride * st->chunk_bytes, c_end - c + 1});
+      runs.push_back({src, stage_at(c, 0), st->chunk_bytes, (size_t)stride * st->chunk_bytes, c_end - c + 1});
       c = c_end + 1;
     }
   };
 
-  // The gather kernel needs a device-readable arena and reads its segment table from pinned
+  // The gather kernel needs device-readable arenas and reads its segment table from pinned
   // host memory; a pageable arena goes through hipMemcpyAsync.
-  const bool use_gather = st->pinned && ctx->loader_mode == 1;
+  const bool use_gather = ctx->loader_mode == 1 && (l_h == 0 || hs->pinned) && (l_h == L || ks->pinned);
   CopySegment* tab = nullptr;
   size_t tab_used = 0;
   int tab_id = 0;
   if (use_gather) {
     tab_id = ctx->seg_next;
     ctx->seg_next ^= 1;
-    const size_t need = (size_t)L * (size_t)(c_last - c_first + 1);
+    size_t need = 0;
+    if (l_h > 0) need += (size_t)l_h * (size_t)((tok_begin + n_tok - 1) / hs->chunk_tokens - tok_begin / hs->chunk_tokens + 1);
+    if (l_h < L) need += (size_t)(L - l_h) * (size_t)((tok_begin + n_tok - 1) / ks->chunk_tokens - tok_begin / ks->chunk_tokens + 1);
     if (!ctx->seg_done[tab_id]) HC_HIP(hipEventCreateWithFlags(&ctx->seg_done[tab_id], hipEventDisableTiming));
     else HC_HIP(hipEventSynchronize(ctx->seg_done[tab_id]));   // kernels of an earlier call still reading it
     if (ctx->seg_cap[tab_id] < need) {
@@ -307,7 +325,9 @@ hc_status hc_restore_context(hc_ctx* ctx, const hc_store* st, int64_t seq_id, in
 
   for (int l = 0; l < L; ++l) {
     const int b = l & 1;
-    build(l, b);
+    const bool from_hidden = l < l_h;
+    if (from_hidden) build(hs, *hseq, l, b);
+    else build(ks, *kseq, l - l_h, b);
     // the kernel that last read stage[b] (two layers ago, or a previous call) must be done
     HC_HIP(hipStreamWaitEvent(xs, ctx->buf_free[b], 0));
     if (use_gather) {
@@ -325,13 +345,50 @@ hc_status hc_restore_context(hc_ctx* ctx, const hc_store* st, int64_t seq_id, in
     }
     HC_HIP(hipEventRecord(ctx->h2d_done[b], xs));
     HC_HIP(hipStreamWaitEvent(cs, ctx->h2d_done[b], 0));
-    hc_status r = restore_layer(ctx, l, ctx->stage[b], nullptr, pos_offset + tok_begin, n_tok,
-                                nullptr, 1, d_block_table, n_blocks, cs);
+    hc_status r = from_hidden
+        ? restore_layer(ctx, l, ctx->stage[b], nullptr, pos_offset + tok_begin, n_tok, nullptr, 1,
+                        d_block_table, n_blocks, cs)
+        : kv_rows_layer(ctx, l, ctx->stage[b], nullptr, pos_offset + tok_begin, n_tok,
+                        d_block_table, n_blocks, true, cs);
     if (r != HC_OK) return r;
     HC_HIP(hipEventRecord(ctx->buf_free[b], cs));
   }
   if (use_gather) HC_HIP(hipEventRecord(ctx->seg_done[tab_id], xs));
   return HC_OK;
+}
+
+hc_status hc_restore_context(hc_ctx* ctx, const hc_store* st, int64_t seq_id, int32_t tok_begin,
+                             int32_t n_tok, int32_t pos_offset, const int32_t* d_block_table,
+                             int32_t n_blocks, void* compute_stream, void* copy_stream) {
+  clear_error();
+  if (!ctx || !st) return fail(HC_EINVAL, "null ctx or store");
+  if (st->n_layers != ctx->desc.n_layers || st->d_model != ctx->desc.d_model)
+    return fail(HC_EINVAL, "store and context disagree on n_layers / d_model");
+  return restore_context_impl(ctx, st, nullptr, ctx->desc.n_layers, seq_id, tok_begin, n_tok,
+                              pos_offset, d_block_table, n_blocks, compute_stream, copy_stream);
+}
+
+hc_status hc_restore_context_mixed(hc_ctx* ctx, const hc_store* hidden_store,
+                                   const hc_store* kv_store, int32_t l_h, int64_t seq_id,
+                                   int32_t tok_begin, int32_t n_tok, int32_t pos_offset,
+                                   const int32_t* d_block_table, int32_t n_blocks,
+                                   void* compute_stream, void* copy_stream) {
+  clear_error();
+  if (!ctx) return fail(HC_EINVAL, "null ctx");
+  const int L = ctx->desc.n_layers;
+  if (l_h < 0 || l_h > L) return fail(HC_ERANGE, "l_h outside [0, n_layers]");
+  if (l_h > 0) {
+    if (!hidden_store) return fail(HC_EINVAL, "hidden-state store is null");
+    if (hidden_store->n_layers < l_h || hidden_store->d_model != ctx->desc.d_model)
+      return fail(HC_EINVAL, "hidden-state store has fewer than l_h layers or another d_model");
+  }
+  if (l_h < L) {
+    if (!kv_store) return fail(HC_EINVAL, "KV store is null");
+    if (kv_store->n_layers != L - l_h || kv_store->d_model != 2 * ctx->d_kv)
+      return fail(HC_EINVAL, "KV store must hold n_layers - l_h layers of 2 * d_kv wide rows");
+  }
+  return restore_context_impl(ctx, hidden_store, kv_store, l_h, seq_id, tok_begin, n_tok,
+                              pos_offset, d_block_table, n_blocks, compute_stream, copy_stream);
 }
 
 }  // extern "C"

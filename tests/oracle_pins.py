@@ -402,6 +402,44 @@ def check_save_step(o):
     assert st.n_chunks(10, 0) == 2 and st.chunk(10, 0, 1).shape == (1, 2)
 
 
+def check_mixed_restore(o):
+    """Layer-wise partition with the KV-offload complement (Section 4.1.2): restoring some
+    layers from hidden states and the others from the K/V a prefill produced gives the cache
+    of restoring everything from hidden states; scatter and gather are inverse."""
+    w = syn.WORKLOADS[0]
+    H0 = syn.bf16_bits_to_f64(syn.layer_hidden(w, 0))[:48]
+    layers = []
+    for l in range(w.n_layers):
+        wkv, g = syn.layer_weights(w, l)
+        d = syn.dense_model_weights(w, l)
+        lay = {k: syn.bf16_bits_to_f64(v) for k, v in d.items()}
+        lay["wkv"], lay["gamma"] = syn.bf16_bits_to_f64(wkv), syn.bf16_bits_to_f64(g)
+        layers.append(lay)
+    pos = np.arange(5, 5 + len(H0))                         # starts mid-page
+    rec = o.full_prefill(H0, layers, pos, eps=w.rms_eps, theta=w.rope_theta,
+                         n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim)
+    n_blocks = (pos[-1] + w.block_size) // w.block_size
+    bt = np.random.default_rng(4).permutation(n_blocks + 3)[:n_blocks]
+    kw = dict(eps=w.rms_eps, theta=w.rope_theta, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+              block_size=w.block_size, rope_style=0)
+    shape = (n_blocks + 3, 2, w.block_size, w.n_kv_heads, w.head_dim)
+    for l, (h_l, k_l, v_l) in enumerate(rec):
+        from_hidden = np.full(shape, np.nan)
+        o.restore_kv(from_hidden, h_l, layers[l]["gamma"], layers[l]["wkv"], pos, bt, **kw)
+        from_kv = np.full(shape, np.nan)
+        o.scatter_kv(from_kv, k_l, v_l, pos, bt, w.block_size)
+        assert np.array_equal(np.isnan(from_hidden), np.isnan(from_kv))
+        m = ~np.isnan(from_kv)
+        assert np.max(np.abs(from_hidden[m] - from_kv[m])) <= 1e-11 * np.max(np.abs(from_kv[m]))
+        # brute force placement and the inverse
+        for t in (0, 10, len(pos) - 1):
+            p, sl = bt[pos[t] // w.block_size], pos[t] % w.block_size
+            assert np.array_equal(from_kv[p, 0, sl], k_l[t]) and np.array_equal(from_kv[p, 1, sl], v_l[t])
+        kk, vv = o.gather_kv(from_kv, pos, bt, w.block_size)
+        assert np.array_equal(kk, k_l) and np.array_equal(vv, v_l)
+        assert m.sum() == 2 * len(pos) * w.d_kv
+
+
 def check_partition(o):
     """The closed forms of Section 4.1.2 against the optimisation problem they claim to solve
     (brute force over every split) and against the schedules of Table 3."""
@@ -466,6 +504,7 @@ ALL_CHECKS = (
     check_ragged,
     check_store,
     check_save_step,
+    check_mixed_restore,
     check_partition,
     check_cost_accounting,
 )

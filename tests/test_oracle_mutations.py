@@ -135,6 +135,11 @@ def mut_save_rows_to_wrong_context(o):
     o.save_step = lambda store, layer, rows, row_seq: real(store, layer, rows, list(row_seq)[::-1])
 
 
+def mut_scatter_kv_swapped(o):
+    real = o.scatter_kv
+    o.scatter_kv = lambda pool, k, v, *a: real(pool, v, k, *a)
+
+
 def mut_partition_floor(o):
     real = o.partition_layers
 
