@@ -27,6 +27,9 @@ written out.  Readings chosen where the paper is silent:
   * paged cache of one layer: pool[page, 0|1 (K|V), slot, kv_head, head_dim] with
     page = block_table[position // block_size], slot = position % block_size.
 
+  * OPT-style layers (LayerNorm with shift, projection biases, no rotary embedding) are the
+    same restoration with layernorm() in place of rmsnorm(), the bias added and no rotation.
+
 Parity pins (tests/test_oracle_*.py): restored KV equals the KV of a naive full
 prefill; pure-Python brute force on tiny inputs; closed forms for RMSNorm; RoPE
 invariants plus a worked rotation; paging bijection/enumeration; store round trip.
@@ -46,6 +49,18 @@ def rmsnorm(x, gamma, eps):
     x = np.asarray(x, dtype=np.float64)
     ms = np.mean(x * x, axis=-1, keepdims=True)
     return x / np.sqrt(ms + eps) * np.asarray(gamma, dtype=np.float64)
+
+
+def layernorm(x, gamma, beta, eps):
+    """Layer normalisation of each row of x [T, d]: (x - mean) / sqrt(var + eps) * gamma + beta
+    with the biased variance var = mean((x - mean)^2).  The normalisation of OPT-style
+    models (the paper evaluates OPT-30B, Section 6 "Models"), whose layers also carry biases
+    and use learned absolute position embeddings instead of RoPE."""
+    x = np.asarray(x, dtype=np.float64)
+    mu = np.mean(x, axis=-1, keepdims=True)
+    xc = x - mu
+    var = np.mean(xc * xc, axis=-1, keepdims=True)
+    return xc / np.sqrt(var + eps) * np.asarray(gamma, dtype=np.float64) + np.asarray(beta, dtype=np.float64)
 
 
 # --------------------------------------------------------------------------- RoPE
@@ -79,15 +94,26 @@ def apply_rope(y, positions, theta, style=0):
 
 
 # ----------------------------------------------------------------- restoration
-def project_kv(x, gamma, wkv, eps, n_kv_heads, head_dim):
+def project_kv(x, gamma, wkv, eps, n_kv_heads, head_dim, *, norm="rms", beta=None, bias=None):
     """K (before RoPE) and V of every token: the restoration equations of Section 3.1
     applied to the normalised hidden state.  wkv is [2*d_kv, d] (nn.Linear layout),
-    rows [0, d_kv) = W_k, rows [d_kv, 2 d_kv) = W_v.  Returns ([T,H,hd], [T,H,hd])."""
+    rows [0, d_kv) = W_k, rows [d_kv, 2 d_kv) = W_v.  Returns ([T,H,hd], [T,H,hd]).
+
+    norm = "rms" (Llama-style, default) or "layer" (OPT-style, with shift beta [d]);
+    bias [2*d_kv], when given, is the projections' bias (b_k then b_v)."""
     d_kv = n_kv_heads * head_dim
     wkv = np.asarray(wkv, dtype=np.float64)
     assert wkv.shape[0] == 2 * d_kv
-    xh = rmsnorm(x, gamma, eps)
+    if norm == "rms":
+        assert beta is None
+        xh = rmsnorm(x, gamma, eps)
+    elif norm == "layer":
+        xh = layernorm(x, gamma, np.zeros(wkv.shape[1]) if beta is None else beta, eps)
+    else:
+        raise ValueError("norm must be 'rms' or 'layer'")
     y = xh @ wkv.T                                     # [T, 2 d_kv]
+    if bias is not None:
+        y = y + np.asarray(bias, dtype=np.float64)
     T = y.shape[0]
     k = y[:, :d_kv].reshape(T, n_kv_heads, head_dim)
     v = y[:, d_kv:].reshape(T, n_kv_heads, head_dim)
@@ -109,13 +135,16 @@ def page_slots(positions, block_table, block_size):
 
 
 def restore_kv(pool, x, gamma, wkv, positions, block_table, *, eps, theta,
-               n_kv_heads, head_dim, block_size, rope_style=0):
+               n_kv_heads, head_dim, block_size, rope_style=0, norm="rms", beta=None, bias=None):
     """Restore one layer's K/V for the tokens of one context into its paged cache.
 
     pool: float64 [num_pages, 2, block_size, n_kv_heads, head_dim], modified in place
-    (only the slots of the given positions are written).  Returns (page, slot)."""
-    k, v = project_kv(x, gamma, wkv, eps, n_kv_heads, head_dim)
-    k = apply_rope(k, positions, theta, rope_style)
+    (only the slots of the given positions are written).  Returns (page, slot).
+    rope_style 2 = no rotation (models with learned absolute position embeddings: the
+    position is already part of the hidden state)."""
+    k, v = project_kv(x, gamma, wkv, eps, n_kv_heads, head_dim, norm=norm, beta=beta, bias=bias)
+    if rope_style != 2:
+        k = apply_rope(k, positions, theta, rope_style)
     page, slot = page_slots(positions, block_table, block_size)
     if page.size and page.max() >= pool.shape[0]:
         raise IndexError("block table names a page outside the pool")
@@ -193,6 +222,37 @@ def full_prefill(h0, layers, positions, *, eps, theta, n_q_heads, n_kv_heads,
         g = xh2 @ lw["w_gate"].T
         u = xh2 @ lw["w_up"].T
         h = h + ((g / (1.0 + np.exp(-g))) * u) @ lw["w_down"].T
+    return record
+
+
+def full_prefill_opt(h0, layers, *, eps, n_heads, head_dim):
+    """Naive prefill of an OPT-style stack (pre-LayerNorm decoder, multi-head attention,
+    biases on every projection, ReLU feed-forward, no rotary embedding: h0 already holds
+    token plus learned position embeddings).  layers: dicts with float64 'wkv' [2d, d],
+    'bkv' [2d], 'gamma', 'beta', 'wq', 'bq', 'wo', 'bo', 'gamma2', 'beta2', 'w1', 'b1',
+    'w2', 'b2'.  Returns per layer (H_l, K_l, V_l) like full_prefill."""
+    h = np.asarray(h0, dtype=np.float64)
+    T = h.shape[0]
+    d_kv = n_heads * head_dim
+    causal = np.tril(np.ones((T, T), dtype=bool))
+    record = []
+    for lw in layers:
+        xh = layernorm(h, lw["gamma"], lw["beta"], eps)
+        q = (xh @ lw["wq"].T + lw["bq"]).reshape(T, n_heads, head_dim)
+        k = (xh @ lw["wkv"][:d_kv].T + lw["bkv"][:d_kv]).reshape(T, n_heads, head_dim)
+        v = (xh @ lw["wkv"][d_kv:].T + lw["bkv"][d_kv:]).reshape(T, n_heads, head_dim)
+        record.append((h.copy(), k.copy(), v.copy()))
+        att = np.empty((T, n_heads, head_dim))
+        for hh in range(n_heads):
+            s = (q[:, hh] @ k[:, hh].T) / np.sqrt(head_dim)
+            s = np.where(causal, s, -np.inf)
+            s = s - s.max(axis=-1, keepdims=True)
+            p = np.exp(s)
+            p /= p.sum(axis=-1, keepdims=True)
+            att[:, hh] = p @ v[:, hh]
+        h = h + att.reshape(T, -1) @ lw["wo"].T + lw["bo"]
+        xh2 = layernorm(h, lw["gamma2"], lw["beta2"], eps)
+        h = h + np.maximum(xh2 @ lw["w1"].T + lw["b1"], 0.0) @ lw["w2"].T + lw["b2"]
     return record
 
 

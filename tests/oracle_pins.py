@@ -313,6 +313,124 @@ def check_prefill_vs_loops(o):
         assert np.allclose(rec[l][2].reshape(T, -1), np.array(v), rtol=1e-11, atol=1e-12)
 
 
+# ------------------------------------------------------------ OPT-style layers
+def check_layernorm(o):
+    """LayerNorm against a worked example, closed forms, invariances and the (separately
+    pinned) RMSNorm it reduces to on zero-mean rows."""
+    # worked by hand: mean 2.5, biased variance 1.25, sqrt = 1.118033988...
+    y = o.layernorm(np.array([[1.0, 2.0, 3.0, 4.0]]), np.ones(4), np.zeros(4), 0.0)
+    assert np.allclose(y, [[-1.3416407865, -0.4472135955, 0.4472135955, 1.3416407865]], atol=1e-9)
+    # eps sits inside the root, added to the variance: var 1.25 + eps 2.75 = 4 -> divide by 2
+    y = o.layernorm(np.array([[1.0, 2.0, 3.0, 4.0]]), np.ones(4), np.zeros(4), 2.75)
+    assert np.allclose(y, [[-0.75, -0.25, 0.25, 0.75]], atol=1e-12)
+    # gain multiplies, shift adds afterwards
+    y = o.layernorm(np.array([[1.0, 2.0, 3.0, 4.0]]), np.array([2.0, 1, 1, -1]), np.array([0.5, 0, 0, 10]), 2.75)
+    assert np.allclose(y, [[-1.0, -0.25, 0.25, 9.25]], atol=1e-12)
+    rng = np.random.default_rng(17)
+    x = rng.standard_normal((6, 24)) * 3 + 1.7
+    g, b = 1 + 0.2 * rng.standard_normal(24), rng.standard_normal(24)
+    y = o.layernorm(x, g, b, 1e-5)
+    assert np.allclose(o.layernorm(x + 123.0, g, b, 1e-5), y, atol=1e-9)         # shift invariant
+    assert np.allclose(o.layernorm(x, np.ones(24), np.zeros(24), 0.0).mean(axis=1), 0, atol=1e-12)
+    assert np.allclose((o.layernorm(x, np.ones(24), np.zeros(24), 0.0) ** 2).mean(axis=1), 1, atol=1e-12)
+    assert np.allclose(o.layernorm(np.full((2, 8), 4.2), g[:8], b[:8], 1e-5), np.tile(b[:8], (2, 1)))
+    xc = x - x.mean(axis=1, keepdims=True)                                     # zero-mean rows
+    assert np.allclose(o.layernorm(xc, g, b, 0.3), o.rmsnorm(xc, g, 0.3) + b, atol=1e-12)
+    # pure Python
+    for t in range(2):
+        row = x[t].tolist()
+        mu = sum(row) / len(row)
+        var = sum((v - mu) ** 2 for v in row) / len(row)
+        want = [(v - mu) / math.sqrt(var + 1e-5) * gg + bb for v, gg, bb in zip(row, g.tolist(), b.tolist())]
+        assert np.allclose(y[t], want, rtol=1e-12, atol=1e-13)
+
+
+def loops_opt_layer(h, lw, *, eps, n_heads, head_dim):
+    """One OPT-style layer in pure Python: returns (next hidden state, K, V) as lists."""
+    T, hd = len(h), head_dim
+
+    def norm(row, gamma, beta):
+        mu = sum(row) / len(row)
+        var = sum((v - mu) ** 2 for v in row) / len(row)
+        return [(v - mu) / math.sqrt(var + eps) * g + b for v, g, b in zip(row, gamma, beta)]
+
+    def mv(mat, vec, bias):
+        return [sum(a * b for a, b in zip(r, vec)) + bb for r, bb in zip(mat, bias)]
+
+    d_kv = n_heads * hd
+    q, k, v = [], [], []
+    for t in range(T):
+        xh = norm(h[t], lw["gamma"], lw["beta"])
+        q.append(mv(lw["wq"], xh, lw["bq"]))
+        k.append(mv(lw["wkv"][:d_kv], xh, lw["bkv"][:d_kv]))
+        v.append(mv(lw["wkv"][d_kv:], xh, lw["bkv"][d_kv:]))
+    out = []
+    for t in range(T):
+        att = []
+        for hh in range(n_heads):
+            sc = [sum(q[t][hh * hd + j] * k[m][hh * hd + j] for j in range(hd)) / math.sqrt(hd)
+                  for m in range(t + 1)]
+            mx = max(sc)
+            e = [math.exp(s - mx) for s in sc]
+            z = sum(e)
+            att += [sum(e[m] / z * v[m][hh * hd + j] for m in range(t + 1)) for j in range(hd)]
+        h1 = [a + b for a, b in zip(h[t], mv(lw["wo"], att, lw["bo"]))]
+        xh2 = norm(h1, lw["gamma2"], lw["beta2"])
+        act = [max(a, 0.0) for a in mv(lw["w1"], xh2, lw["b1"])]
+        out.append([a + b for a, b in zip(h1, mv(lw["w2"], act, lw["b2"]))])
+    return out, k, v
+
+
+def opt_layers(rng, n, d, H, hd, dff):
+    layers = []
+    for _ in range(n):
+        layers.append({
+            "wkv": rng.standard_normal((2 * H * hd, d)) * 0.4, "bkv": rng.standard_normal(2 * H * hd) * 0.3,
+            "gamma": 1 + 0.1 * rng.standard_normal(d), "beta": 0.2 * rng.standard_normal(d),
+            "wq": rng.standard_normal((H * hd, d)) * 0.4, "bq": rng.standard_normal(H * hd) * 0.3,
+            "wo": rng.standard_normal((d, H * hd)) * 0.4, "bo": rng.standard_normal(d) * 0.3,
+            "gamma2": 1 + 0.1 * rng.standard_normal(d), "beta2": 0.2 * rng.standard_normal(d),
+            "w1": rng.standard_normal((dff, d)) * 0.4, "b1": rng.standard_normal(dff) * 0.3,
+            "w2": rng.standard_normal((d, dff)) * 0.4, "b2": rng.standard_normal(d) * 0.3,
+        })
+    return layers
+
+
+def check_opt_style(o):
+    """OPT-style restoration (LayerNorm + shift, biases, no rotation): the vectorised prefill
+    against a scalar one, and restoration from each layer's saved input against the KV that
+    prefill holds (lossless), through the paged cache."""
+    rng = np.random.default_rng(23)
+    T, d, H, hd, dff, B = 5, 8, 2, 4, 12, 4
+    layers = opt_layers(rng, 2, d, H, hd, dff)
+    h0 = rng.standard_normal((T, d)) + 0.8                  # rows with a clear non-zero mean
+    rec = o.full_prefill_opt(h0, layers, eps=1e-5, n_heads=H, head_dim=hd)
+    h = h0.tolist()
+    for l, lw in enumerate(layers):
+        lwl = {k: v.tolist() for k, v in lw.items()}
+        assert np.allclose(rec[l][0], np.array(h), rtol=1e-11, atol=1e-12), l
+        h, k, v = loops_opt_layer(h, lwl, eps=1e-5, n_heads=H, head_dim=hd)
+        assert np.allclose(rec[l][1].reshape(T, -1), np.array(k), rtol=1e-11, atol=1e-12)
+        assert np.allclose(rec[l][2].reshape(T, -1), np.array(v), rtol=1e-11, atol=1e-12)
+    pos = np.array([6, 7, 8, 9, 10])
+    bt = np.array([2, 0, 3])
+    for l, (h_l, k_l, v_l) in enumerate(rec):
+        pool = np.full((4, 2, B, H, hd), np.nan)
+        o.restore_kv(pool, h_l, layers[l]["gamma"], layers[l]["wkv"], pos, bt, eps=1e-5, theta=10000.0,
+                     n_kv_heads=H, head_dim=hd, block_size=B, rope_style=2, norm="layer",
+                     beta=layers[l]["beta"], bias=layers[l]["bkv"])
+        gk, gv = o.gather_kv(pool, pos, bt, B)
+        assert np.max(np.abs(gk - k_l)) <= 1e-12 * np.max(np.abs(k_l)), l
+        assert np.max(np.abs(gv - v_l)) <= 1e-12 * np.max(np.abs(v_l)), l
+        assert (~np.isnan(pool)).sum() == 2 * T * H * hd
+    # RMSNorm with a projection bias (Qwen-style): identity weights give normalised input + bias
+    x = rng.standard_normal((3, 8))
+    gamma, bias = rng.standard_normal(8), rng.standard_normal(8)
+    k, v = o.project_kv(x, gamma, np.eye(8), 0.5, 1, 4, bias=bias)
+    xh = x / np.sqrt(np.mean(x * x, axis=1, keepdims=True) + 0.5) * gamma + bias
+    assert np.allclose(np.concatenate([k.reshape(3, 4), v.reshape(3, 4)], axis=1), xh)
+
+
 # ----------------------------------------------------------------------- GEMM
 def check_projection_reduces_to_matmul(o):
     """gamma = 1, eps = 0 and rows of unit mean square: the normalisation is the
@@ -504,6 +622,8 @@ ALL_CHECKS = (
     check_ragged,
     check_store,
     check_save_step,
+    check_layernorm,
+    check_opt_style,
     check_mixed_restore,
     check_partition,
     check_cost_accounting,

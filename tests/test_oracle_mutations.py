@@ -135,6 +135,39 @@ def mut_save_rows_to_wrong_context(o):
     o.save_step = lambda store, layer, rows, row_seq: real(store, layer, rows, list(row_seq)[::-1])
 
 
+def mut_layernorm_uncentred_variance(o):
+    def layernorm(x, gamma, beta, eps):
+        x = np.asarray(x, dtype=np.float64)
+        mu = np.mean(x, axis=-1, keepdims=True)
+        return (x - mu) / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + eps) * gamma + beta
+    o.layernorm = layernorm
+
+
+def mut_layernorm_unbiased_variance(o):
+    def layernorm(x, gamma, beta, eps):
+        x = np.asarray(x, dtype=np.float64)
+        xc = x - np.mean(x, axis=-1, keepdims=True)
+        var = np.sum(xc * xc, axis=-1, keepdims=True) / (x.shape[-1] - 1)
+        return xc / np.sqrt(var + eps) * gamma + beta
+    o.layernorm = layernorm
+
+
+def mut_layernorm_shift_before_gain(o):
+    real = o.layernorm
+    o.layernorm = lambda x, gamma, beta, eps: real(x, gamma, np.zeros_like(np.asarray(beta, dtype=float)), eps) + \
+        np.asarray(beta) * np.asarray(gamma)
+
+
+def mut_bias_dropped(o):
+    real = o.project_kv
+    o.project_kv = lambda *a, **kw: real(*a, **{**kw, "bias": None})
+
+
+def mut_rotation_kept_without_rope(o):
+    real = o.restore_kv
+    o.restore_kv = lambda *a, **kw: real(*a, **{**kw, "rope_style": 0 if kw.get("rope_style") == 2 else kw.get("rope_style", 0)})
+
+
 def mut_scatter_kv_swapped(o):
     real = o.scatter_kv
     o.scatter_kv = lambda pool, k, v, *a: real(pool, v, k, *a)
