@@ -66,8 +66,13 @@ typedef struct hc_saver hc_saver;
 /* Shape of the model whose KV cache is restored.  Supported by the kernels:
  * d_model % 64 == 0, head_dim % 64 == 0, block_size a power of two, n_q_heads % n_kv_heads
  * == 0.  rope_style 0 pairs feature i with i + head_dim/2, 1 pairs 2i with 2i+1 (the
- * paper only cites RoFormer; both conventions are in use).  The RoPE table is built
- * for positions [0, max_position). */
+ * paper only cites RoFormer; both conventions are in use), 2 applies no rotation (models
+ * with learned absolute position embeddings such as OPT, one of the paper's test models,
+ * Section 6 "Models"; positions then only address the cache).  The RoPE table is built for
+ * positions [0, max_position).  norm_kind selects the layer's input normalisation:
+ * HC_NORM_RMS (x / sqrt(mean x^2 + eps) * gain) or HC_NORM_LAYER ((x - mean) / sqrt(var + eps)
+ * * gain + shift, biased variance); rms_eps is the eps of either. */
+enum { HC_NORM_RMS = 0, HC_NORM_LAYER = 1 };
 typedef struct {
   int32_t n_layers;
   int32_t d_model;
@@ -79,6 +84,7 @@ typedef struct {
   int32_t rope_style;
   float   rope_theta;
   float   rms_eps;
+  int32_t norm_kind;
 } hc_model_desc;
 
 /* Message describing the last failure on the calling thread ("" if none). */
@@ -108,6 +114,17 @@ hc_status hc_destroy(hc_ctx* ctx);
  * for the same layer replaces the weights. */
 hc_status hc_set_layer_weights(hc_ctx* ctx, int32_t layer, const void* d_wkv,
                                const void* d_gamma, void* stream);
+
+/* The same for layers with additive terms (OPT-style: LayerNorm shift and projection biases;
+ * RMSNorm models with K/V biases):
+ *   d_beta bf16 [d_model]  shift of the input LayerNorm; NULL = none; must be NULL under
+ *                          HC_NORM_RMS (HC_EINVAL)
+ *   d_bias bf16 [2*d_kv]   bias of the K then the V projection; NULL = none
+ * K = W_k * norm(x) + b_k (then rotated unless rope_style = 2), V = W_v * norm(x) + b_v.  The
+ * library folds the additive terms into one fp32 constant per output feature. */
+hc_status hc_set_layer_weights_affine(hc_ctx* ctx, int32_t layer, const void* d_wkv,
+                                      const void* d_gamma, const void* d_beta,
+                                      const void* d_bias, void* stream);
 
 /* Register one layer's paged KV pool (borrowed, never freed by the library):
  *   d_pool bf16 [num_pages][2 (0=K,1=V)][block_size][n_kv_heads][head_dim]            */

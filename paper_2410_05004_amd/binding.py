@@ -7,6 +7,7 @@ _LIB_FILE = os.path.join(HERE, "libhcache.so")
 
 HC_OK, HC_EINVAL, HC_ERANGE, HC_EALIGN, HC_ENOMEM, HC_EHIP, HC_ESTATE = 0, -1, -2, -3, -4, -5, -6
 HC_DEV_BAD_POSITION, HC_DEV_BAD_PAGE = 1, 2
+HC_NORM_RMS, HC_NORM_LAYER = 0, 1
 _STATUS_NAMES = {0: "HC_OK", -1: "HC_EINVAL", -2: "HC_ERANGE", -3: "HC_EALIGN", -4: "HC_ENOMEM",
                  -5: "HC_EHIP", -6: "HC_ESTATE"}
 
@@ -23,7 +24,7 @@ class ModelDesc(C.Structure):
         ("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
         ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("block_size", C.c_int32),
         ("max_position", C.c_int32), ("rope_style", C.c_int32),
-        ("rope_theta", C.c_float), ("rms_eps", C.c_float),
+        ("rope_theta", C.c_float), ("rms_eps", C.c_float), ("norm_kind", C.c_int32),
     ]
 
 
@@ -54,6 +55,7 @@ def _load():
         "hc_create": (i32, [p(ModelDesc), p(vp)]),
         "hc_destroy": (i32, [vp]),
         "hc_set_layer_weights": (i32, [vp, i32, vp, vp, vp]),
+        "hc_set_layer_weights_affine": (i32, [vp, i32, vp, vp, vp, vp, vp]),
         "hc_set_kv_pool": (i32, [vp, i32, vp, i64]),
         "hc_restore_kv": (i32, [vp, i32, vp, vp, i32, vp, i32, vp]),
         "hc_restore_kv_ragged": (i32, [vp, i32, vp, vp, i32, vp, i32, vp, i32, vp]),
@@ -93,7 +95,7 @@ EXPORTED = ("hc_last_error hc_version hc_validate_desc hc_create hc_destroy hc_s
             "hc_store_drop hc_restore_context hc_set_loader hc_timing_begin hc_timing_end "
             "hc_saver_create hc_saver_destroy hc_saver_save_layer hc_saver_save_layer_host "
             "hc_saver_flush hc_partition_layers hc_gather_kv hc_scatter_kv "
-            "hc_restore_context_mixed").split()
+            "hc_restore_context_mixed hc_set_layer_weights_affine").split()
 
 
 def _check(status):
@@ -151,6 +153,10 @@ class Context:
 
     def set_layer_weights(self, layer, d_wkv, d_gamma, stream=0):
         _check(lib.hc_set_layer_weights(self._h, layer, _ptr(d_wkv), _ptr(d_gamma), stream))
+
+    def set_layer_weights_affine(self, layer, d_wkv, d_gamma, d_beta, d_bias, stream=0):
+        _check(lib.hc_set_layer_weights_affine(self._h, layer, _ptr(d_wkv), _ptr(d_gamma),
+                                               _ptr(d_beta), _ptr(d_bias), stream))
 
     def set_kv_pool(self, layer, d_pool, num_pages):
         _check(lib.hc_set_kv_pool(self._h, layer, _ptr(d_pool), num_pages))

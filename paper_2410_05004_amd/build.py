@@ -8,7 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhcache.so")
-SOURCES = ["api.cpp", "store.cpp", "saver.cpp", "restore_kernel.hip", "aux_kernels.hip"]
+SOURCES = ["api.cpp", "store.cpp", "saver.cpp", "restore_mode0.hip", "restore_mode1.hip",
+           "restore_mode2.hip", "aux_kernels.hip"]
 
 
 def hipcc_path():
@@ -19,25 +20,44 @@ def hipcc_path():
 
 
 def build(verbose=False, extra_flags=()):
-    """Compile every source for gfx950 and link the shared library. Always recompiles."""
-    cmd = [
-        hipcc_path(), "-x", "hip", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    """Compile every source for gfx950 (one hipcc process per file, in parallel) and link the
+    shared library.  Always recompiles."""
+    from concurrent.futures import ThreadPoolExecutor
+    obj_dir = os.path.join(HERE, "_build")
+    os.makedirs(obj_dir, exist_ok=True)
+    common = [
+        hipcc_path(), "-x", "hip", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
         "-Wall", "-Wno-unused-result", "-pthread",
         # packed fp32 ALU forms are kept out of the generated code on purpose
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-        "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-        *extra_flags,
-        *[os.path.join(CSRC, s) for s in SOURCES],
-        "-o", LIB,
+        "-I", os.path.join(ROOT, "include"), "-I", CSRC, *extra_flags,
     ]
+
+    def compile_one(src):
+        obj = os.path.join(obj_dir, os.path.splitext(src)[0] + ".o")
+        cmd = common + ["-c", os.path.join(CSRC, src), "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        return obj, subprocess.run(cmd, capture_output=True, text=True)
+
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1, 16)) as pool:
+        results = list(pool.map(compile_one, SOURCES))
+    failed = [r for _, r in results if r.returncode != 0]
+    if failed:
+        for r in failed:
+            sys.stderr.write(r.stdout + r.stderr)
+        raise RuntimeError("hipcc failed")
     if verbose:
-        print(" ".join(cmd), flush=True)
-    res = subprocess.run(cmd, capture_output=True, text=True)
+        for _, r in results:
+            sys.stderr.write(r.stderr)
+    link = [hipcc_path(), "--offload-arch=gfx950", "-shared", "-fPIC", "-pthread",
+            *[o for o, _ in results], "-o", LIB]
+    if verbose:
+        print(" ".join(link), flush=True)
+    res = subprocess.run(link, capture_output=True, text=True)
     if res.returncode != 0:
         sys.stderr.write(res.stdout + res.stderr)
-        raise RuntimeError("hipcc failed")
-    if verbose and res.stderr:
-        sys.stderr.write(res.stderr)
+        raise RuntimeError("link failed")
     return LIB
 
 

@@ -36,8 +36,10 @@ static hc_status check_desc(const hc_model_desc* d) {
   if (d->max_position <= 0) return fail(HC_EINVAL, "max_position must be positive");
   if ((int64_t)d->max_position * (d->head_dim / 2) * 8 > ((int64_t)1 << 34))
     return fail(HC_EINVAL, "RoPE table would exceed 16 GiB");
-  if (d->rope_style != 0 && d->rope_style != 1)
-    return fail(HC_EINVAL, "rope_style must be 0 (half-split) or 1 (interleaved)");
+  if (d->rope_style < 0 || d->rope_style > 2)
+    return fail(HC_EINVAL, "rope_style must be 0 (half-split), 1 (interleaved) or 2 (none)");
+  if (d->norm_kind != HC_NORM_RMS && d->norm_kind != HC_NORM_LAYER)
+    return fail(HC_EINVAL, "norm_kind must be HC_NORM_RMS or HC_NORM_LAYER");
   if (!(d->rope_theta > 0.f)) return fail(HC_EINVAL, "rope_theta must be positive");
   if (!(d->rms_eps >= 0.f)) return fail(HC_EINVAL, "rms_eps must be non-negative");
   if ((int64_t)d->n_kv_heads * d->head_dim > (1 << 20))
@@ -66,6 +68,8 @@ hc_status restore_layer(hc_ctx* ctx, int32_t layer, const void* d_hidden,
   a.cu_seqlens = d_cu;
   a.block_tables = d_tables;
   a.rope = ctx->rope;
+  a.affine = L.affine;
+  a.mode = ctx->desc.norm_kind == HC_NORM_LAYER ? 2 : (L.affine ? 1 : 0);
   a.pool = L.pool;
   a.err = ctx->err_dev;
   a.num_pages = L.num_pages;
@@ -153,12 +157,13 @@ hc_status hc_create(const hc_model_desc* desc, hc_ctx** out) {
 
   hipError_t e = hipGetDevice(&ctx->device);
   if (e == hipSuccess) e = configure_kernels();
-  if (e == hipSuccess)
+  const bool rotary = desc->rope_style != 2;
+  if (e == hipSuccess && rotary)
     e = hipMalloc(reinterpret_cast<void**>(&ctx->rope),
                   (size_t)desc->max_position * (desc->head_dim / 2) * sizeof(float2));
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->err_dev), 256);
   if (e == hipSuccess) e = hipMemset(ctx->err_dev, 0, 256);
-  if (e == hipSuccess)
+  if (e == hipSuccess && rotary)
     e = launch_rope_table(ctx->rope, desc->max_position, desc->head_dim, (double)desc->rope_theta,
                           nullptr);
   if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
@@ -177,8 +182,10 @@ hc_status hc_destroy(hc_ctx* ctx) {
   clear_error();
   if (!ctx) return HC_OK;
   (void)hipDeviceSynchronize();
-  for (auto& L : ctx->layers)
+  for (auto& L : ctx->layers) {
     if (L.wpack) (void)hipFree(L.wpack);
+    if (L.affine) (void)hipFree(L.affine);
+  }
   if (ctx->rope) (void)hipFree(ctx->rope);
   if (ctx->err_dev) (void)hipFree(ctx->err_dev);
   for (int i = 0; i < 2; ++i) {
@@ -197,12 +204,41 @@ hc_status hc_destroy(hc_ctx* ctx) {
 
 hc_status hc_set_layer_weights(hc_ctx* ctx, int32_t layer, const void* d_wkv, const void* d_gamma,
                                void* stream) {
+  return hc_set_layer_weights_affine(ctx, layer, d_wkv, d_gamma, nullptr, nullptr, stream);
+}
+
+hc_status hc_set_layer_weights_affine(hc_ctx* ctx, int32_t layer, const void* d_wkv,
+                                      const void* d_gamma, const void* d_beta,
+                                      const void* d_bias, void* stream) {
   clear_error();
   hc_status s = check_layer(ctx, layer);
   if (s != HC_OK) return s;
   if (!d_wkv || !d_gamma) return fail(HC_EINVAL, "weight pointer is null");
   if (!aligned16(d_wkv) || !aligned16(d_gamma)) return fail(HC_EALIGN, "weights not 16-byte aligned");
+  const bool layer_norm = ctx->desc.norm_kind == HC_NORM_LAYER;
+  if (d_beta && !layer_norm) return fail(HC_EINVAL, "a shift needs norm_kind = HC_NORM_LAYER");
   hc_layer_state& L = ctx->layers[layer];
+  // LayerNorm always needs the row sums; RMSNorm needs the table only for a bias
+  const bool need_affine = layer_norm || d_bias;
+  if (need_affine && !L.affine) {
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&L.affine), (size_t)ctx->n_phys * sizeof(float2));
+    if (e != hipSuccess) {
+      L.affine = nullptr;
+      (void)hipGetLastError();
+      return fail(HC_ENOMEM, "device allocation of the row constants failed");
+    }
+  }
+  if (!need_affine && L.affine) {
+    // replaced by plain weights; kernels already queued may still read the table
+    HC_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+    HC_HIP(hipFree(L.affine));
+    L.affine = nullptr;
+  }
+  if (need_affine)
+    HC_HIP(launch_pack_affine(static_cast<const uint16_t*>(d_wkv), static_cast<const uint16_t*>(d_gamma),
+                              static_cast<const uint16_t*>(d_beta), static_cast<const uint16_t*>(d_bias),
+                              L.affine, ctx->desc.d_model, ctx->d_kv, ctx->desc.head_dim,
+                              ctx->desc.rope_style, static_cast<hipStream_t>(stream)));
   if (!L.wpack) {
     const size_t bytes = (size_t)ctx->n_phys * ctx->desc.d_model * sizeof(uint16_t);
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&L.wpack), bytes);

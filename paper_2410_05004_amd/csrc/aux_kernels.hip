@@ -31,8 +31,18 @@ __device__ __forceinline__ int logical_row(int p, int d_kv, int d_kv_pad, int hd
   const int gph = hd >> 6;
   const int head = grp / gph, qq = grp - head * gph;
   const int pair = 32 * qq + u;
-  const int f = style == 0 ? head * hd + member * (hd >> 1) + pair : head * hd + 2 * pair + member;
+  // style 2 (no rotation) shares the half-split order
+  const int f = style != 1 ? head * hd + member * (hd >> 1) + pair : head * hd + 2 * pair + member;
   return part * d_kv + f;
+}
+
+// bf16( W * gamma ), round to nearest even: the value the matrix cores multiply with
+__device__ __forceinline__ uint16_t fold_gain(uint16_t w_bits, uint16_t g_bits) {
+  const float prod = __uint_as_float((uint32_t)w_bits << 16) * __uint_as_float((uint32_t)g_bits << 16);
+  uint32_t u = __float_as_uint(prod);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;     // NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
 }
 
 __global__ __launch_bounds__(256) void pack_weights_kernel(const uint16_t* __restrict__ wkv,
@@ -42,19 +52,7 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const uint16_t* __res
   const int p = blockIdx.x;                               // physical row
   const int src = logical_row(p, d_kv, d_kv_pad, hd, style);
   for (int c = threadIdx.x; c < d_model; c += blockDim.x) {
-    uint16_t out = 0;
-    if (src >= 0) {
-      const float w = __uint_as_float((uint32_t)wkv[(size_t)src * d_model + c] << 16);
-      const float g = __uint_as_float((uint32_t)gamma[c] << 16);
-      const float prod = w * g;
-      uint32_t u = __float_as_uint(prod);
-      if ((u & 0x7fffffffu) > 0x7f800000u) {
-        out = 0x7fc0;                                     // NaN
-      } else {
-        u += 0x7fffu + ((u >> 16) & 1u);                  // round to nearest even
-        out = (uint16_t)(u >> 16);
-      }
-    }
+    const uint16_t out = src >= 0 ? fold_gain(wkv[(size_t)src * d_model + c], gamma[c]) : (uint16_t)0;
     const int tile_f = p >> 8, r = p & 255, kt = c >> 5, chunk = (c >> 3) & 3, e = c & 7;
     const size_t tile = (size_t)tile_f * (d_model >> 5) + kt;
     wpack[tile * (kWTileBytes / 2) + r * 32 + ((chunk ^ swz_w(r)) << 3) + e] = out;
@@ -67,6 +65,52 @@ hipError_t launch_pack_weights(const uint16_t* wkv, const uint16_t* gamma, uint1
   const int d_kv_pad = round_up(d_kv, kPartAlign);
   hipLaunchKernelGGL(pack_weights_kernel, dim3(2 * d_kv_pad), dim3(256), 0, stream, wkv, gamma,
                      wpack, d_model, d_kv, d_kv_pad, head_dim, rope_style);
+  return hipGetLastError();
+}
+
+// Row constants of the affine variants (LayerNorm shift, projection bias), in fp64 and rounded
+// once: S[n] = sum_c W'[n,c] over exactly the rounded values the pack kernel stores (so that
+// mean * S cancels the mean's share of the accumulator), C[n] = sum_c W[n,c] beta[c] + bias[n].
+__global__ __launch_bounds__(256) void pack_affine_kernel(const uint16_t* __restrict__ wkv,
+                                                          const uint16_t* __restrict__ gamma,
+                                                          const uint16_t* __restrict__ beta,
+                                                          const uint16_t* __restrict__ bias,
+                                                          float2* __restrict__ affine, int d_model,
+                                                          int d_kv, int d_kv_pad, int hd, int style) {
+  __shared__ double red[2][256];
+  const int p = blockIdx.x;
+  const int src = logical_row(p, d_kv, d_kv_pad, hd, style);
+  double s = 0.0, c0 = 0.0;
+  if (src >= 0) {
+    for (int c = threadIdx.x; c < d_model; c += 256) {
+      const uint16_t w = wkv[(size_t)src * d_model + c];
+      s += (double)__uint_as_float((uint32_t)fold_gain(w, gamma[c]) << 16);
+      if (beta) c0 += (double)__uint_as_float((uint32_t)w << 16) * (double)__uint_as_float((uint32_t)beta[c] << 16);
+    }
+  }
+  red[0][threadIdx.x] = s;
+  red[1][threadIdx.x] = c0;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) {
+      red[0][threadIdx.x] += red[0][threadIdx.x + w];
+      red[1][threadIdx.x] += red[1][threadIdx.x + w];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    double c = red[1][0];
+    if (src >= 0 && bias) c += (double)__uint_as_float((uint32_t)bias[src] << 16);
+    affine[p] = make_float2((float)red[0][0], (float)c);
+  }
+}
+
+hipError_t launch_pack_affine(const uint16_t* wkv, const uint16_t* gamma, const uint16_t* beta,
+                              const uint16_t* bias, float2* affine, int d_model, int d_kv,
+                              int head_dim, int rope_style, hipStream_t stream) {
+  const int d_kv_pad = round_up(d_kv, kPartAlign);
+  hipLaunchKernelGGL(pack_affine_kernel, dim3(2 * d_kv_pad), dim3(256), 0, stream, wkv, gamma, beta,
+                     bias, affine, d_model, d_kv, d_kv_pad, head_dim, rope_style);
   return hipGetLastError();
 }
 

@@ -40,7 +40,8 @@ struct RestoreArgs {
   const int32_t* positions;      // [n_tok] or nullptr: position = pos_base + row
   const int32_t* cu_seqlens;     // [n_seq + 1] or nullptr (single context)
   const int32_t* block_tables;   // [n_seq][max_blocks]
-  const float2* rope;            // [max_position][head_dim/2] (cos, sin)
+  const float2* rope;            // [max_position][head_dim/2] (cos, sin); unused when rope_style = 2
+  const float2* affine;          // [n_phys] per packed row: (sum of the row, constant term); modes 1, 2
   uint16_t* pool;                // bf16 [num_pages][2][block_size][n_kv_heads][head_dim]
   int32_t* err;                  // sticky error word (device-visible host memory)
   int64_t num_pages;
@@ -54,7 +55,8 @@ struct RestoreArgs {
   int32_t d_kv_pad;              // d_kv rounded up to kPartAlign
   int32_t head_dim;
   int32_t block_shift;           // log2(block_size)
-  int32_t rope_style;
+  int32_t rope_style;            // 0 half-split, 1 interleaved, 2 no rotation
+  int32_t mode;                  // 0 RMSNorm, 1 RMSNorm + bias, 2 LayerNorm + bias
   float inv_d;                   // 1 / d_model
   float eps;
 };
@@ -64,6 +66,11 @@ hipError_t launch_restore(const RestoreArgs& a, hipStream_t stream);
 hipError_t launch_pack_weights(const uint16_t* wkv, const uint16_t* gamma, uint16_t* wpack,
                                int d_model, int d_kv, int head_dim, int rope_style,
                                hipStream_t stream);
+// Per packed row n: (sum_c W'[n,c], sum_c W[n,c] * beta[c] + bias[n]) with W' the rounded,
+// gain-folded weights the pack kernel writes; beta and bias may be null (zeros).
+hipError_t launch_pack_affine(const uint16_t* wkv, const uint16_t* gamma, const uint16_t* beta,
+                              const uint16_t* bias, float2* affine, int d_model, int d_kv,
+                              int head_dim, int rope_style, hipStream_t stream);
 hipError_t launch_rope_table(float2* table, int max_position, int head_dim, double theta,
                              hipStream_t stream);
 hipError_t configure_kernels();   // one-time function attributes (dynamic LDS size)
@@ -121,6 +128,7 @@ hc_status kv_rows_layer(hc_ctx* ctx, int32_t layer, void* d_rows, const int32_t*
 
 struct hc_layer_state {
   uint16_t* wpack = nullptr;     // owned
+  float2* affine = nullptr;      // owned; present when the layer has a shift or a bias, or LayerNorm
   uint16_t* pool = nullptr;      // borrowed
   int64_t num_pages = 0;
 };

@@ -11,6 +11,7 @@ from .workloads import (
     WORKLOADS,
     BASE_SEED,
     layer_weights,
+    layer_affine,
     layer_hidden,
     block_table,
     ragged_lengths,
@@ -27,6 +28,7 @@ __all__ = [
     "WORKLOADS",
     "BASE_SEED",
     "layer_weights",
+    "layer_affine",
     "layer_hidden",
     "block_table",
     "ragged_lengths",

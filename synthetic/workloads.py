@@ -1,8 +1,9 @@
 """Shapes and seeded tensors of the synthetic restoration workloads.
 
-The five workloads mirror the model shapes the paper evaluates (Llama-2-7B/13B,
+The first five workloads mirror the model shapes the paper evaluates (Llama-2-7B/13B,
 Section 6 "Experimental Setup") and the context-length statistics it reports for
-its traces (Section 2.3), plus a GQA and a 70B-shaped long-context case.  All
+its traces (Section 2.3), plus a GQA and a 70B-shaped long-context case; the sixth has
+the shape and layer style of OPT-30B, the paper's third test model.  All
 tensors are random: the cost and the numerics of the restoration path depend on
 shapes and value distributions only, not on trained weights.
 
@@ -17,7 +18,7 @@ from .bf16 import f32_to_bf16_bits
 BASE_SEED = 20241005
 
 # tensor-kind keys of the random sub-streams
-_K_WKV, _K_GAMMA, _K_HIDDEN, _K_OUTLIER, _K_BLOCKS, _K_LENGTHS, _K_DENSE = range(7)
+_K_WKV, _K_GAMMA, _K_HIDDEN, _K_OUTLIER, _K_BLOCKS, _K_LENGTHS, _K_DENSE, _K_AFFINE = range(8)
 
 
 @dataclass(frozen=True)
@@ -38,6 +39,9 @@ class Workload:
     rms_eps: float = 1e-5
     block_size: int = 16
     d_ff: int = 0               # only the tiny workload runs a full forward pass
+    norm: str = "rms"           # "rms" (Llama-style) or "layer" (OPT-style: shift and biases too)
+    rope_style: int = 0         # 0 half-split, 1 interleaved, 2 none (learned absolute positions)
+    hidden_mean: float = 0.0    # offset added to every hidden-state element
 
     @property
     def d_kv(self):
@@ -62,6 +66,9 @@ WORKLOADS = (
              n_seq=16, len_range=(512, 4096)),
     Workload(4, "70b-gqa-T32768", 80, 8192, 64, 8, 128, 500000.0, 32768,
              pos_offset=1000, chunk_tokens=512),
+    # the paper's third test model (OPT-30B): LayerNorm, biases, no rotary embedding, MHA
+    Workload(5, "opt30b-T2048", 48, 7168, 56, 56, 128, 10000.0, 2048,
+             norm="layer", rope_style=2, hidden_mean=0.25),
 )
 
 
@@ -89,6 +96,13 @@ def layer_weights(w, layer):
     return wkv, gamma
 
 
+def layer_affine(w, layer):
+    """(beta [d_model], bias [2*d_kv]) of an OPT-style layer as bf16 bits: the LayerNorm shift
+    ~ N(0, 0.05^2) and the K|V projection bias ~ N(0, 0.05^2)."""
+    r = _rng(w, _K_AFFINE, layer)
+    return _normal_bf16(r, (w.d_model,), 0.0, 0.05), _normal_bf16(r, (w.n_out,), 0.0, 0.05)
+
+
 def outlier_channels(w, layer):
     """Sorted channel indices that carry the x20 outliers of this layer (1% of d_model)."""
     n = int(round(0.01 * w.d_model))
@@ -114,6 +128,8 @@ def layer_hidden(w, layer, n_tokens=None, token_offset=0):
     lo = token_offset - first * blk
     x = x[lo:lo + n_tokens]
     x[:, outlier_channels(w, layer)] *= np.float32(20.0)
+    if w.hidden_mean != 0.0:
+        x += np.float32(w.hidden_mean)
     return f32_to_bf16_bits(x)
 
 

@@ -42,9 +42,9 @@ def stream_handle():
 
 
 def make_desc(hc, *, n_layers, d_model, n_q_heads, n_kv_heads, head_dim, block_size=16,
-              max_position=4096, rope_style=0, rope_theta=10000.0, rms_eps=1e-5):
+              max_position=4096, rope_style=0, rope_theta=10000.0, rms_eps=1e-5, norm_kind=0):
     return hc.ModelDesc(n_layers, d_model, n_q_heads, n_kv_heads, head_dim, block_size,
-                        max_position, rope_style, rope_theta, rms_eps)
+                        max_position, rope_style, rope_theta, rms_eps, norm_kind)
 
 
 def desc_of_workload(hc, w, max_position=None, rope_style=0):
@@ -60,7 +60,7 @@ def oracle_kw(desc):
     # theta and eps as the float32 values the library received
     return dict(eps=float(np.float32(desc.rms_eps)), theta=float(np.float32(desc.rope_theta)),
                 n_kv_heads=desc.n_kv_heads, head_dim=desc.head_dim, block_size=desc.block_size,
-                rope_style=desc.rope_style)
+                rope_style=desc.rope_style, norm="layer" if desc.norm_kind == 1 else "rms")
 
 
 def compare_pool(gpu_bits, ora_pool, tol=TOL):

@@ -36,8 +36,10 @@ def sample_rows(rng, T, edges, first_page, last_page, n_random=1024):
     return np.array(sorted(rows), dtype=np.int64)
 
 
-def check_layer(w, desc, bits, x_bits, wkv_bits, gamma_bits, pos, seq_of_row, tables, rows, rng):
-    """bits: GPU pool uint16 [P,2,B,H,hd]; pos/seq_of_row per token; tables [n_seq, max_blocks]."""
+def check_layer(w, desc, bits, x_bits, wkv_bits, gamma_bits, pos, seq_of_row, tables, rows, rng,
+                beta_bits=None, bias_bits=None):
+    """bits: GPU pool uint16 [P,2,B,H,hd]; pos/seq_of_row per token; tables [n_seq, max_blocks];
+    beta_bits / bias_bits: LayerNorm shift and projection bias of the affine variants."""
     kw = gh.oracle_kw(desc)
     B, H, hd = desc.block_size, desc.n_kv_heads, desc.head_dim
     T = len(pos)
@@ -62,8 +64,11 @@ def check_layer(w, desc, bits, x_bits, wkv_bits, gamma_bits, pos, seq_of_row, ta
     # (ii) sampled tokens, every feature
     xf = syn.bf16_bits_to_f64(x_bits)                          # [T, d]
     xs = xf[rows]
-    k, v = oracle.project_kv(xs, gamma, wkv, kw["eps"], H, hd)
-    k = oracle.apply_rope(k, pos[rows], kw["theta"], kw["rope_style"])
+    beta = None if beta_bits is None else syn.bf16_bits_to_f64(beta_bits)
+    bias = None if bias_bits is None else syn.bf16_bits_to_f64(bias_bits)
+    k, v = oracle.project_kv(xs, gamma, wkv, kw["eps"], H, hd, norm=kw["norm"], beta=beta, bias=bias)
+    if kw["rope_style"] != 2:
+        k = oracle.apply_rope(k, pos[rows], kw["theta"], kw["rope_style"])
     worst = 0.0
     rms_kv = []
     for ref, g in ((k, got[rows, 0]), (v, got[rows, 1])):
@@ -76,12 +81,21 @@ def check_layer(w, desc, bits, x_bits, wkv_bits, gamma_bits, pos, seq_of_row, ta
     # (iii) random projection over all tokens
     r = rng.standard_normal(H * hd)
     d_kv = H * hd
-    xh_scale = 1.0 / np.sqrt(np.einsum("td,td->t", xf, xf) / xf.shape[1] + kw["eps"])
+    if kw["norm"] == "rms":
+        mu = np.zeros(T)
+        xh_scale = 1.0 / np.sqrt(np.einsum("td,td->t", xf, xf) / xf.shape[1] + kw["eps"])
+    else:
+        mu = xf.mean(axis=1)
+        xh_scale = 1.0 / np.sqrt(xf.var(axis=1) + kw["eps"])
     proj = []
     for part in (0, 1):
-        u = (wkv[part * d_kv:(part + 1) * d_kv].T @ r) * gamma          # [d]
-        proj.append((xf @ u) * xh_scale)                                # [T]
-    k_unrot = oracle.apply_rope(got[:, 0], -pos.astype(np.int64), kw["theta"], kw["rope_style"])
+        wr = wkv[part * d_kv:(part + 1) * d_kv].T @ r                   # [d]
+        u = wr * gamma
+        const = (0.0 if beta is None else wr @ beta) + \
+            (0.0 if bias is None else bias[part * d_kv:(part + 1) * d_kv] @ r)
+        proj.append((xf @ u - mu * u.sum()) * xh_scale + const)         # [T]
+    k_unrot = got[:, 0] if kw["rope_style"] == 2 else \
+        oracle.apply_rope(got[:, 0], -pos.astype(np.int64), kw["theta"], kw["rope_style"])
     dk = np.abs(k_unrot.reshape(T, -1) @ r - proj[0])
     dv = np.abs(got[:, 1].reshape(T, -1) @ r - proj[1])
     lim_k = gh.TOL * rms_kv[0] * np.linalg.norm(r)

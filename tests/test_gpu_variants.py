@@ -1,0 +1,134 @@
+"""GPU parity of the layer-style variants of the restoration kernel against the fp64 oracle:
+LayerNorm with shift, projection biases and no rotation (OPT-style, the paper's third test
+model), and their combinations with RMSNorm and the two RoPE conventions."""
+import numpy as np
+import pytest
+
+import synthetic as syn
+import oracle.hcache_oracle as oracle
+import gpu_harness as gh
+from test_gpu_fullsize import check_layer, sample_rows
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hc():
+    import paper_2410_05004_amd as m
+    return m
+
+
+def bf16(rng, shape, mean, std):
+    return syn.f32_to_bf16_bits((mean + std * rng.standard_normal(shape)).astype(np.float32))
+
+
+VARIANTS = [
+    # norm_kind, rope_style, shift, bias
+    (1, 2, True, True),        # OPT
+    (1, 2, False, False),      # LayerNorm alone
+    (1, 0, True, True),        # LayerNorm + rotary (GPT-NeoX-like)
+    (1, 1, False, True),
+    (0, 0, False, True),       # RMSNorm + K/V bias (Qwen-like)
+    (0, 1, False, True),
+    (0, 2, False, False),      # RMSNorm, no rotation
+    (0, 2, False, True),
+]
+
+
+@pytest.mark.parametrize("norm_kind,rope_style,shift,with_bias", VARIANTS)
+def test_variant_matches_oracle(hc, norm_kind, rope_style, shift, with_bias):
+    """Every element of a 3-tile x 3-tile problem with ragged tails (d_kv = 640 pads the K and
+    V parts), rows with a clearly non-zero mean, unsorted positions."""
+    rng = np.random.default_rng([5, norm_kind, rope_style, shift, with_bias])
+    d_model, n_kv, hd, B, T = 1024, 5, 128, 16, 600
+    d_kv = n_kv * hd
+    n_blocks = 64
+    desc = gh.make_desc(hc, n_layers=1, d_model=d_model, n_q_heads=n_kv, n_kv_heads=n_kv, head_dim=hd,
+                        block_size=B, max_position=n_blocks * B, rope_style=rope_style,
+                        norm_kind=norm_kind)
+    wkv = bf16(rng, (2 * d_kv, d_model), 0.0, 0.02)
+    gamma = bf16(rng, (d_model,), 1.0, 0.1)
+    beta = bf16(rng, (d_model,), 0.0, 0.05) if shift else None
+    bias = bf16(rng, (2 * d_kv,), 0.0, 0.05) if with_bias else None
+    x = bf16(rng, (T, d_model), 0.4, 1.0)
+    pos = rng.permutation(n_blocks * B)[:T].astype(np.int32)
+    num_pages = n_blocks + 9
+    bt = rng.permutation(num_pages)[:n_blocks].astype(np.int32)
+    ctx = hc.Context(desc)
+    s = gh.stream_handle()
+    pool = gh.new_pool(num_pages, B, n_kv, hd)
+    ctx.set_kv_pool(0, pool, num_pages)
+    dev = [gh.to_dev_bf16(a) if a is not None else None for a in (wkv, gamma, beta, bias)]
+    if shift or with_bias or norm_kind == 1:
+        ctx.set_layer_weights_affine(0, dev[0], dev[1], dev[2], dev[3], s)
+    else:
+        ctx.set_layer_weights(0, dev[0], dev[1], s)
+    ctx.restore_kv(0, gh.to_dev_bf16(x), gh.to_dev_i32(pos), T, gh.to_dev_i32(bt), n_blocks, s)
+    assert ctx.poll_device_error(s) == 0
+    ora = np.full((num_pages, 2, B, n_kv, hd), np.nan)
+    f = syn.bf16_bits_to_f64
+    oracle.restore_kv(ora, f(x), f(gamma), f(wkv), pos, bt,
+                      beta=None if beta is None else f(beta), bias=None if bias is None else f(bias),
+                      **gh.oracle_kw(desc))
+    worst = gh.compare_pool(gh.pool_bits(pool), ora)
+    print(f"variant norm={norm_kind} rope={rope_style} shift={shift} bias={with_bias}: "
+          f"worst error {worst * gh.TOL:.4f} x RMS", flush=True)
+    ctx.destroy()
+
+
+def test_affine_argument_errors(hc):
+    desc = gh.make_desc(hc, n_layers=1, d_model=256, n_q_heads=2, n_kv_heads=2, head_dim=64)
+    ctx = hc.Context(desc)
+    s = gh.stream_handle()
+    rng = np.random.default_rng(3)
+    w, g = gh.to_dev_bf16(bf16(rng, (256, 256), 0, 0.02)), gh.to_dev_bf16(bf16(rng, (256,), 1, 0.1))
+    b = gh.to_dev_bf16(bf16(rng, (256,), 0, 0.1))
+    with pytest.raises(hc.HCacheError) as e:               # a shift under RMSNorm
+        ctx.set_layer_weights_affine(0, w, g, b, None, s)
+    assert e.value.status == hc.HC_EINVAL
+    ctx.set_layer_weights_affine(0, w, g, None, b, s)      # bias, then back to plain weights
+    ctx.set_layer_weights(0, w, g, s)
+    ctx.destroy()
+    for bad in (dict(rope_style=3), dict(norm_kind=2), dict(norm_kind=-1)):
+        with pytest.raises(hc.HCacheError) as e:
+            hc.validate_desc(gh.make_desc(hc, n_layers=1, d_model=256, n_q_heads=2, n_kv_heads=2,
+                                          head_dim=64, **bad))
+        assert e.value.status == hc.HC_EINVAL
+
+
+def test_opt30b_shape(hc):
+    """The OPT-30B shape at full width (d_model 7168, 56 heads, 2048 tokens), first and last
+    layer: whole-pool indexing, sampled rows element by element, random projection over all
+    tokens."""
+    import torch
+    w = syn.WORKLOADS[5]
+    T, B = w.tokens, w.block_size
+    layers = (0, w.n_layers - 1)
+    desc = gh.make_desc(hc, n_layers=len(layers), d_model=w.d_model, n_q_heads=w.n_q_heads,
+                        n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, block_size=B,
+                        max_position=T, rope_style=w.rope_style, rms_eps=w.rms_eps, norm_kind=1)
+    ctx = hc.Context(desc)
+    s = gh.stream_handle()
+    bt, num_pages = syn.block_table(w, T)
+    d_bt = gh.to_dev_i32(bt)
+    pos = np.arange(T, dtype=np.int32)
+    d_pos = gh.to_dev_i32(pos)
+    rng = np.random.default_rng(55)
+    rows = sample_rows(rng, T, [256 * i for i in range(1, T // 256)], range(B), range(T - B, T), 256)
+    for i, l in enumerate(layers):
+        wkv, gamma = syn.layer_weights(w, l)
+        beta, bias = syn.layer_affine(w, l)
+        x = syn.layer_hidden(w, l)
+        ctx.set_layer_weights_affine(i, gh.to_dev_bf16(wkv), gh.to_dev_bf16(gamma),
+                                     gh.to_dev_bf16(beta), gh.to_dev_bf16(bias), s)
+        torch.cuda.synchronize()
+        pool = gh.new_pool(num_pages, B, w.n_kv_heads, w.head_dim)
+        ctx.set_kv_pool(i, pool, num_pages)
+        ctx.restore_kv(i, gh.to_dev_bf16(x), d_pos, T, d_bt, len(bt), s)
+        assert ctx.poll_device_error(s) == 0
+        res = check_layer(w, desc, gh.pool_bits(pool), x, wkv, gamma, pos, np.zeros(T, dtype=np.int64),
+                          bt[None, :], rows, rng, beta_bits=beta, bias_bits=bias)
+        print(f"{w.name} layer {l}: sampled {res[0]:.4f} x RMS, projection {res[1]:.3f} / {res[2]:.3f} of limit",
+              flush=True)
+        del pool
+    ctx.destroy()

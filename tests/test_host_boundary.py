@@ -39,17 +39,19 @@ def test_version_and_error_string(hc):
 
 def good_desc(hc, **over):
     kw = dict(n_layers=2, d_model=256, n_q_heads=4, n_kv_heads=4, head_dim=64, block_size=16,
-              max_position=128, rope_style=0, rope_theta=10000.0, rms_eps=1e-5)
+              max_position=128, rope_style=0, rope_theta=10000.0, rms_eps=1e-5, norm_kind=0)
     kw.update(over)
     return hc.ModelDesc(*[kw[k] for k in ("n_layers", "d_model", "n_q_heads", "n_kv_heads",
                                            "head_dim", "block_size", "max_position", "rope_style",
-                                           "rope_theta", "rms_eps")])
+                                           "rope_theta", "rms_eps", "norm_kind")])
 
 
 def test_desc_validation(hc):
     hc.validate_desc(good_desc(hc))
+    hc.validate_desc(good_desc(hc, rope_style=2, norm_kind=1))
     bad = [dict(n_layers=0), dict(d_model=100), dict(head_dim=48), dict(n_q_heads=6, n_kv_heads=4),
-           dict(block_size=12), dict(max_position=0), dict(rope_style=2), dict(rope_theta=0.0),
+           dict(block_size=12), dict(max_position=0), dict(rope_style=3), dict(rope_theta=0.0),
+           dict(norm_kind=2),
            dict(rms_eps=-1.0), dict(n_kv_heads=0)]
     for over in bad:
         with pytest.raises(hc.HCacheError) as e:
