@@ -39,8 +39,9 @@ def main():
         sys.exit("sweep_tokens: no GPU visible")
     w = syn.WORKLOADS[args.workload]
     T = args.max_tokens
-    desc = hc.ModelDesc(1, w.d_model, w.n_q_heads, w.n_kv_heads, w.head_dim, w.block_size, T, 0,
-                        w.rope_theta, w.rms_eps)
+    layer_norm = w.norm == "layer"
+    desc = hc.ModelDesc(1, w.d_model, w.n_q_heads, w.n_kv_heads, w.head_dim, w.block_size, T,
+                        w.rope_style, w.rope_theta, w.rms_eps, 1 if layer_norm else 0)
     ctx = hc.Context(desc)
     s = torch.cuda.current_stream().cuda_stream
     wkv, gamma = syn.layer_weights(w, 0)
@@ -48,7 +49,13 @@ def main():
     d_w = torch.from_numpy(wkv.view(np.int16)).cuda()
     d_g = torch.from_numpy(gamma.view(np.int16)).cuda()
     d_x = torch.from_numpy(x.view(np.int16)).cuda()
-    ctx.set_layer_weights(0, d_w, d_g, s)
+    if layer_norm:                                          # OPT-style: shift and biases too
+        beta, bias = syn.layer_affine(w, 0)
+        d_b = torch.from_numpy(beta.view(np.int16)).cuda()
+        d_c = torch.from_numpy(bias.view(np.int16)).cuda()
+        ctx.set_layer_weights_affine(0, d_w, d_g, d_b, d_c, s)
+    else:
+        ctx.set_layer_weights(0, d_w, d_g, s)
     n_blocks = (T + w.block_size - 1) // w.block_size
     pool = torch.zeros((n_blocks, 2, w.block_size, w.n_kv_heads, w.head_dim), dtype=torch.bfloat16, device="cuda")
     ctx.set_kv_pool(0, pool, n_blocks)
