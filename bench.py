@@ -28,7 +28,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16, vendor figure without s
 # HBM-side traffic of one restore_kernel launch, from two rocprofv3 --pmc runs (FETCH_SIZE, then
 # WRITE_SIZE, each scaled by what the counter reads for a plain 256 MiB streaming kernel):
 # profiles/restore_kernel_llama3-8b-gqa-T8192.md.  Bytes per launch; None where not profiled.
-TRAFFIC_BYTES_PER_LAUNCH = {"llama3-8b-gqa-T8192": 2.394e8}
+TRAFFIC_BYTES_PER_LAUNCH = {"llama3-8b-gqa-T8192": 2.436e8}
 
 
 def log(*a):
@@ -44,7 +44,10 @@ def cpu_baseline(w, sample_tokens):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count()
-    T = min(sample_tokens, w.tokens)
+    # ragged workload: the first tokens of its first context stand for the batch (rows are
+    # independent, the cost per token is the same)
+    avail = w.tokens if w.n_seq == 1 else int(syn.ragged_lengths(w)[0])
+    T = min(sample_tokens, avail)
     bt, num_pages = syn.block_table(w, w.pos_offset + T)
     pos = w.pos_offset + np.arange(T)
     pool = np.zeros((num_pages, 2, w.block_size, w.n_kv_heads, w.head_dim))
@@ -53,9 +56,14 @@ def cpu_baseline(w, sample_tokens):
         wkv, gamma = syn.layer_weights(w, l)
         x = syn.bf16_bits_to_f64(syn.layer_hidden(w, l, T))
         wkv, gamma = syn.bf16_bits_to_f64(wkv), syn.bf16_bits_to_f64(gamma)
+        extra = {}
+        if w.norm == "layer":
+            beta, bias = syn.layer_affine(w, l)
+            extra = dict(norm="layer", beta=syn.bf16_bits_to_f64(beta), bias=syn.bf16_bits_to_f64(bias))
         t0 = time.perf_counter()
         oracle.restore_kv(pool, x, gamma, wkv, pos, bt, eps=w.rms_eps, theta=w.rope_theta,
-                          n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, block_size=w.block_size)
+                          n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, block_size=w.block_size,
+                          rope_style=w.rope_style, **extra)
         total += time.perf_counter() - t0
     return {"value": T / total, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
             "sample": f"all {w.n_layers} layers x first {T} tokens of the workload, fp64 numpy, "
@@ -93,15 +101,22 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the restoration path has no CPU fallback")
     w = syn.WORKLOADS[args.workload]
-    if w.n_seq != 1:
-        sys.exit("bench.py: ragged workloads are covered by the parity tests, not the bench line")
+    ragged = w.n_seq != 1
+    if ragged:
+        args.no_e2e = True                                  # the store path restores one context at a time
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    T, L, d = w.tokens, w.n_layers, w.d_model
+    L, d = w.n_layers, w.d_model
+    if ragged:
+        lengths = syn.ragged_lengths(w)
+        T, max_pos = int(lengths.sum()), int(lengths.max())
+    else:
+        T, max_pos = w.tokens, w.pos_offset + w.tokens
     log(f"workload {w.name}: L={L} d={d} d_kv={w.d_kv} T={T}")
 
     desc = hc.ModelDesc(L, d, w.n_q_heads, w.n_kv_heads, w.head_dim, w.block_size,
-                        w.pos_offset + T, 0, w.rope_theta, w.rms_eps)
+                        max_pos, w.rope_style, w.rope_theta, w.rms_eps,
+                        hc.HC_NORM_LAYER if w.norm == "layer" else hc.HC_NORM_RMS)
     ctx = hc.Context(desc)
     stream = torch.cuda.current_stream().cuda_stream
 
@@ -110,18 +125,36 @@ def main():
 
     # ---- synthetic inputs (seeded), resident in HBM before anything is timed
     t0 = time.time()
-    bt, num_pages = syn.block_table(w, w.pos_offset + T)
-    d_bt = torch.from_numpy(bt).to(dev)
-    d_pos = torch.arange(w.pos_offset, w.pos_offset + T, dtype=torch.int32, device=dev)
+    if ragged:
+        tables, num_pages = syn.ragged_block_tables(w, lengths)
+        d_bt = torch.from_numpy(tables).to(dev)
+        d_cu = torch.from_numpy(np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)).to(dev)
+        d_pos = torch.from_numpy(np.concatenate([np.arange(n, dtype=np.int32) for n in lengths])).to(dev)
+        bt = tables
+    else:
+        bt, num_pages = syn.block_table(w, w.pos_offset + T)
+        d_bt = torch.from_numpy(bt).to(dev)
+        d_pos = torch.arange(w.pos_offset, w.pos_offset + T, dtype=torch.int32, device=dev)
     pools, hidden_dev, hidden_host = [], [], []
-    with ThreadPoolExecutor(min(16, os.cpu_count() or 8)) as ex:
-        gen = list(ex.map(lambda l: (syn.layer_weights(w, l), syn.layer_hidden(w, l)), range(L)))
-    for l, ((wkv, gamma), x) in enumerate(gen):
+    def generate(l):
+        return syn.layer_weights(w, l), syn.layer_hidden(w, l, T)
+    workers = min(8, os.cpu_count() or 8)                  # a few layers at a time: bounded host memory
+    pool_ex = ThreadPoolExecutor(workers)
+    gen = {}
+    for l in range(L):
+        if l % workers == 0:
+            gen = dict(zip(range(l, min(L, l + workers)), pool_ex.map(generate, range(l, min(L, l + workers)))))
+        (wkv, gamma), x = gen.pop(l)
         if args.zero_inputs:
             wkv[:] = 0
             x[:] = 0
         d_w, d_g = dev_bf16(wkv), dev_bf16(gamma)
-        ctx.set_layer_weights(l, d_w, d_g, stream)
+        if w.norm == "layer":
+            beta, bias = syn.layer_affine(w, l)
+            d_b, d_c = dev_bf16(beta), dev_bf16(bias)
+            ctx.set_layer_weights_affine(l, d_w, d_g, d_b, d_c, stream)
+        else:
+            ctx.set_layer_weights(l, d_w, d_g, stream)
         torch.cuda.synchronize()
         del d_w, d_g
         pool = torch.zeros((num_pages, 2, w.block_size, w.n_kv_heads, w.head_dim),
@@ -129,8 +162,9 @@ def main():
         ctx.set_kv_pool(l, pool, num_pages)
         pools.append(pool)
         hidden_dev.append(dev_bf16(x))
-        hidden_host.append(x)
-    del gen
+        if not args.no_e2e:
+            hidden_host.append(x)
+    pool_ex.shutdown()
     log(f"inputs generated and uploaded in {time.time() - t0:.1f} s")
 
     if args.calibrate_copy:
@@ -147,7 +181,11 @@ def main():
     def step(use=None):
         use = use or lanes
         for l in range(L):
-            ctx.restore_kv(l, hidden_dev[l], d_pos, T, d_bt, len(bt), use[l % len(use)])
+            if ragged:
+                ctx.restore_kv_ragged(l, hidden_dev[l], d_pos, T, d_cu, w.n_seq, d_bt, bt.shape[1],
+                                      use[l % len(use)])
+            else:
+                ctx.restore_kv(l, hidden_dev[l], d_pos, T, d_bt, len(bt), use[l % len(use)])
 
     for _ in range(args.warmup):
         step()
