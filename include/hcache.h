@@ -267,6 +267,18 @@ hc_status hc_saver_destroy(hc_saver* saver);
 hc_status hc_saver_save_layer(hc_saver* saver, int32_t layer, const void* d_hidden, int32_t n_rows,
                               const int64_t* h_row_seq, void* compute_stream, void* down_stream);
 
+/* The same without the wait on `compute_stream`: the layer whose inputs are being snapshot
+ * keeps running beside the copy, and the caller calls hc_saver_fence(saver, stream) before the
+ * first operator that overwrites the buffer -- in the paper's pipeline the first operator of
+ * the NEXT layer (Section 5 "Pipelined state transmission").  hc_saver_fence makes `stream`
+ * wait for every snapshot copy queued so far that no stream has been made to wait for; it
+ * enqueues waits only and never blocks the host.  Overwriting a buffer without the fence
+ * races with its copy. */
+hc_status hc_saver_save_layer_deferred(hc_saver* saver, int32_t layer, const void* d_hidden,
+                                       int32_t n_rows, const int64_t* h_row_seq,
+                                       void* compute_stream, void* down_stream);
+hc_status hc_saver_fence(hc_saver* saver, void* stream);
+
 /* Same for rows that already sit in host memory (stage 2 only; works without a GPU). */
 hc_status hc_saver_save_layer_host(hc_saver* saver, int32_t layer, const void* h_rows,
                                    int32_t n_rows, const int64_t* h_row_seq);

@@ -77,6 +77,8 @@ def _load():
         "hc_saver_create": (i32, [vp, i32, i32, i32, p(vp)]),
         "hc_saver_destroy": (i32, [vp]),
         "hc_saver_save_layer": (i32, [vp, i32, vp, i32, vp, vp, vp]),
+        "hc_saver_save_layer_deferred": (i32, [vp, i32, vp, i32, vp, vp, vp]),
+        "hc_saver_fence": (i32, [vp, vp]),
         "hc_saver_save_layer_host": (i32, [vp, i32, vp, i32, vp]),
         "hc_saver_flush": (i32, [vp]),
         "hc_timing_begin": (i32, [vp]),
@@ -95,7 +97,8 @@ EXPORTED = ("hc_last_error hc_version hc_validate_desc hc_create hc_destroy hc_s
             "hc_store_drop hc_restore_context hc_set_loader hc_timing_begin hc_timing_end "
             "hc_saver_create hc_saver_destroy hc_saver_save_layer hc_saver_save_layer_host "
             "hc_saver_flush hc_partition_layers hc_gather_kv hc_scatter_kv "
-            "hc_restore_context_mixed hc_set_layer_weights_affine").split()
+            "hc_restore_context_mixed hc_set_layer_weights_affine hc_saver_save_layer_deferred "
+            "hc_saver_fence").split()
 
 
 def _check(status):
@@ -268,6 +271,13 @@ class Saver:
     def save_layer(self, layer, d_hidden, n_rows, h_row_seq, compute_stream, down_stream):
         _check(lib.hc_saver_save_layer(self._h, layer, _ptr(d_hidden), n_rows, _ptr(h_row_seq),
                                        compute_stream, down_stream))
+
+    def save_layer_deferred(self, layer, d_hidden, n_rows, h_row_seq, compute_stream, down_stream):
+        _check(lib.hc_saver_save_layer_deferred(self._h, layer, _ptr(d_hidden), n_rows,
+                                                _ptr(h_row_seq), compute_stream, down_stream))
+
+    def fence(self, stream):
+        _check(lib.hc_saver_fence(self._h, stream))
 
     def save_layer_host(self, layer, h_rows, n_rows, h_row_seq):
         _check(lib.hc_saver_save_layer_host(self._h, layer, _ptr(h_rows), n_rows, _ptr(h_row_seq)))

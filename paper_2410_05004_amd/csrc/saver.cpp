@@ -49,6 +49,7 @@ struct hc_saver {
   std::vector<hipEvent_t> ev_ready;   // recorded on the compute stream, waited by the downstream stream
   std::vector<hipEvent_t> ev_copied;  // recorded on the downstream stream after the snapshot copy
   std::vector<char> slot_busy;
+  std::vector<int> unfenced;          // slots whose snapshot copy no compute stream waits for yet
 
   std::mutex m;
   std::condition_variable cv_work, cv_idle;
@@ -248,8 +249,19 @@ hc_status hc_saver_destroy(hc_saver* sv) {
   return HC_OK;
 }
 
-hc_status hc_saver_save_layer(hc_saver* sv, int32_t layer, const void* d_hidden, int32_t n_rows,
-                              const int64_t* h_row_seq, void* compute_stream, void* down_stream) {
+// Make `stream` wait for every snapshot copy no stream has been made to wait for yet.
+static hipError_t fence_snapshots(hc_saver* sv, hipStream_t stream) {
+  for (int slot : sv->unfenced) {
+    hipError_t e = hipStreamWaitEvent(stream, sv->ev_copied[slot], 0);
+    if (e != hipSuccess) return e;
+  }
+  sv->unfenced.clear();
+  return hipSuccess;
+}
+
+static hc_status save_layer_impl(hc_saver* sv, int32_t layer, const void* d_hidden, int32_t n_rows,
+                                 const int64_t* h_row_seq, void* compute_stream, void* down_stream,
+                                 bool fence_now) {
   clear_error();
   hc_status s = check_save_args(sv, layer, d_hidden, n_rows, h_row_seq);
   if (s != HC_OK) return s;
@@ -274,8 +286,14 @@ hc_status hc_saver_save_layer(hc_saver* sv, int32_t layer, const void* d_hidden,
     e = hipMemcpyAsync(sv->slot_buf[slot], d_hidden, (size_t)n_rows * sv->row_bytes,
                        hipMemcpyDeviceToHost, ds);                // ONE copy for the whole batch
   if (e == hipSuccess) e = hipEventRecord(sv->ev_copied[slot], ds);
-  // later work on the compute stream may overwrite the activation buffer only after the copy
-  if (e == hipSuccess) e = hipStreamWaitEvent(cs, sv->ev_copied[slot], 0);
+  if (e == hipSuccess) {
+    // a reused slot's event has just been re-recorded; keep it listed once
+    bool listed = false;
+    for (int u : sv->unfenced) listed = listed || u == slot;
+    if (!listed) sv->unfenced.push_back(slot);
+    // later work on the compute stream may overwrite the activation buffer only after the copy
+    if (fence_now) e = fence_snapshots(sv, cs);
+  }
   if (e != hipSuccess) {
     release();
     return fail_hip(e, "hc_saver_save_layer");
@@ -283,6 +301,25 @@ hc_status hc_saver_save_layer(hc_saver* sv, int32_t layer, const void* d_hidden,
   job->slot = slot;
   job->copied = sv->ev_copied[slot];
   submit(sv, job);
+  return HC_OK;
+}
+
+hc_status hc_saver_save_layer(hc_saver* sv, int32_t layer, const void* d_hidden, int32_t n_rows,
+                              const int64_t* h_row_seq, void* compute_stream, void* down_stream) {
+  return save_layer_impl(sv, layer, d_hidden, n_rows, h_row_seq, compute_stream, down_stream, true);
+}
+
+hc_status hc_saver_save_layer_deferred(hc_saver* sv, int32_t layer, const void* d_hidden,
+                                       int32_t n_rows, const int64_t* h_row_seq,
+                                       void* compute_stream, void* down_stream) {
+  return save_layer_impl(sv, layer, d_hidden, n_rows, h_row_seq, compute_stream, down_stream, false);
+}
+
+hc_status hc_saver_fence(hc_saver* sv, void* stream) {
+  clear_error();
+  if (!sv) return fail(HC_EINVAL, "saver is null");
+  if (sv->device < 0) return HC_OK;                      // host-only saver: nothing is in flight
+  HC_HIP(fence_snapshots(sv, static_cast<hipStream_t>(stream)));
   return HC_OK;
 }
 

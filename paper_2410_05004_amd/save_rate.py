@@ -6,6 +6,8 @@ requires that saving stays off the critical path of generation.  This script pus
 a given shape through hc_saver_save_layer as fast as the library accepts them -- no model
 compute in between -- and reports the sustained snapshot + re-chunking rate for a prefill-shaped
 batch (many rows of one context) and a decode-shaped batch (one row each of many contexts).
+A third part runs a stand-in for the layers' forward compute and shows what saving adds to the
+compute stream's time with and without the deferred fence.
 
     python -m paper_2410_05004_amd.save_rate [--workload 3] [--threads 8]
 """
@@ -52,6 +54,52 @@ def run(hc, torch, w, rows_per_step, n_ctx, steps, threads, chunk_tokens):
             "producer_blocked_fraction": round(t_enq / dt, 3)}
 
 
+def overlap(hc, torch, w, rows, steps, threads, chunk_tokens):
+    """Cost of saving on the compute stream: a stand-in for one layer's forward compute (12
+    [rows, d] x [d, d] products = the 24 N D^2 flop of a layer) runs per layer, (a) alone,
+    (b) with hc_saver_save_layer, whose wait makes the layer start after its snapshot copy,
+    (c) with hc_saver_save_layer_deferred and the fence before the next layer, the paper's
+    event discipline.  Returns ms per step (all layers) for each."""
+    L, d = w.n_layers, w.d_model
+    cap = L * (-(-rows * steps // chunk_tokens)) + 8
+    act = torch.randn((rows, d), device="cuda").to(torch.bfloat16)
+    wmat = (torch.randn((d, d), device="cuda") * 0.02).to(torch.bfloat16)
+    out = torch.empty_like(act)
+    row_seq = np.zeros(rows, dtype=np.int64)
+    compute = torch.cuda.current_stream().cuda_stream
+    down = torch.cuda.Stream()
+
+    def layer_compute():
+        for _ in range(12):
+            torch.mm(act, wmat, out=out)
+
+    res = {}
+    for mode in ("no_saving", "blocking", "deferred"):
+        store = hc.Store(L, d, chunk_tokens, cap, pinned=True)
+        saver = hc.Saver(store, rows, n_slots=8, n_threads=threads)
+        for rep in range(2):                             # first pass warms up, second is timed
+            if rep == 1:
+                saver.flush()
+                store.drop(0) if store.tokens(0, 0) else None
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+            for _ in range(steps):
+                for l in range(L):
+                    if mode == "blocking":
+                        saver.save_layer(l, act, rows, row_seq, compute, down.cuda_stream)
+                    elif mode == "deferred":
+                        saver.save_layer_deferred(l, act, rows, row_seq, compute, down.cuda_stream)
+                    layer_compute()
+                    if mode == "deferred":
+                        saver.fence(compute)
+            torch.cuda.synchronize()
+        res[mode] = round((time.perf_counter() - t0) * 1e3 / steps, 3)
+        saver.flush()
+        saver.destroy()
+        store.destroy()
+    return {"rows_per_step": rows, "steps": steps, "ms_per_step_all_layers": res}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", type=int, default=3)
@@ -66,7 +114,8 @@ def main():
     out = {"workload": w.name, "d_model": w.d_model, "layers": w.n_layers, "threads": args.threads,
            "paper_required_GBps": 3.0,
            "prefill": run(hc, torch, w, 1024, 1, 9, args.threads, 64),
-           "decode": run(hc, torch, w, 64, 64, 65, args.threads, 64)}
+           "decode": run(hc, torch, w, 64, 64, 65, args.threads, 64),
+           "beside_compute": overlap(hc, torch, w, 1024, 4, args.threads, 64)}
     print(json.dumps(out))
 
 

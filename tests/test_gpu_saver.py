@@ -40,12 +40,20 @@ def test_save_then_restore_round_trip(hc):
     compute = torch.cuda.current_stream()
     down = torch.cuda.Stream()
     act = torch.empty((max_rows, d_model), dtype=torch.bfloat16, device="cuda")   # the reused activation buffer
-    for st in steps:
+    scratch = torch.empty_like(act)
+    for i, st in enumerate(steps):
         row_seq = np.concatenate([np.full(n, s, dtype=np.int64) for s, _, n in st])
         n_rows = len(row_seq)
         for l in range(L):
             torch.cat([dev[s][l][a:a + n] for s, a, n in st], out=act[:n_rows])
-            saver.save_layer(l, act, n_rows, row_seq, compute.cuda_stream, down.cuda_stream)
+            if i % 2 == 0:
+                saver.save_layer(l, act, n_rows, row_seq, compute.cuda_stream, down.cuda_stream)
+            else:
+                # the paper's pipeline: the layer runs beside its snapshot (here: it reads the
+                # buffer), and the first operator that overwrites it waits for the copy
+                saver.save_layer_deferred(l, act, n_rows, row_seq, compute.cuda_stream, down.cuda_stream)
+                torch.mul(act, 2.0, out=scratch)
+                saver.fence(compute.cuda_stream)
             act.fill_(-1.0)                             # the next layer overwrites the buffer at once
             rows = np.concatenate([cases[s][l].x_bits[a:a + n] for s, a, n in st])
             oracle.save_step(ref, l, rows, row_seq)

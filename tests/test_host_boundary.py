@@ -157,3 +157,14 @@ def test_partition_matches_oracle(hc):
         with pytest.raises(hc.HCacheError) as e:
             hc.partition_layers(*bad)
         assert e.value.status == hc.HC_EINVAL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU; asking the benchmark for more must say so and fail."""
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                         capture_output=True, text=True, timeout=120)
+    assert res.returncode != 0
+    assert "one GPU" in res.stderr
+    assert res.stdout.strip() == ""
