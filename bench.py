@@ -3,7 +3,7 @@
 
 A step = one restoration of the whole workload: for every layer, the fused kernel
 (RMSNorm -> K|V projection -> RoPE -> paged scatter) over all tokens, hidden states
-already resident in HBM.  `value` is restored tokens per second over all layers.
+already resident in HBM; the layers of a step go out in one launch per 32 layers.  `value` is restored tokens per second over all layers.
 The same JSON line carries the roofline of the dominant kernel (measured with HIP
 events around every launch), the fp64 oracle timed on the host cores on a bounded
 sample, and the PCIe-inclusive end-to-end figure (chunk store -> H2D -> kernel,
@@ -27,8 +27,12 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16, vendor figure without s
 
 # HBM-side traffic of one restore_kernel launch, from two rocprofv3 --pmc runs (FETCH_SIZE, then
 # WRITE_SIZE, each scaled by what the counter reads for a plain 256 MiB streaming kernel):
-# profiles/restore_kernel_llama3-8b-gqa-T8192.md.  Bytes per launch; None where not profiled.
+# profiles/restore_kernel_llama3-8b-gqa-T8192.md.  Bytes per layer (a launch over several layers
+# moves that many times as much); None where not profiled.
 TRAFFIC_BYTES_PER_LAUNCH = {"llama3-8b-gqa-T8192": 2.436e8}
+# the same per layer inside a launch over 32 layers (the compute units run out of step and share
+# less in the per-XCD L2)
+TRAFFIC_BYTES_PER_LAYER_FUSED = {"llama3-8b-gqa-T8192": 3.213e8}
 
 
 def log(*a):
@@ -83,6 +87,10 @@ def main():
     ap.add_argument("--e2e-steps", type=int, default=5)
     ap.add_argument("--streams", type=int, default=1,
                     help="streams the per-layer launches of a step are dealt over (layers are independent)")
+    ap.add_argument("--layers-per-launch", type=int, default=32,
+                    help="layers restored by one kernel launch (hidden states of all layers are resident "
+                         "in HBM here, so they can go out together: hc_restore_kv_layers); 1 = one launch "
+                         "per layer (hc_restore_kv), as the pipelined loader issues them")
     ap.add_argument("--loader", type=int, default=0, help="0 = copy engines, strided runs (default), 1 = gather kernel")
     ap.add_argument("--zero-inputs", action="store_true",
                     help="diagnostic: all-zero hidden states and weights (same instruction stream, no "
@@ -179,8 +187,16 @@ def main():
     side = [torch.cuda.Stream() for _ in range(args.streams - 1)]
     lanes = [stream] + [s_.cuda_stream for s_ in side]
 
+    G = max(1, min(args.layers_per_launch, L))
+    if ragged:
+        G = 1
+
     def step(use=None):
         use = use or lanes
+        if G > 1:
+            for i, l0 in enumerate(range(0, L, G)):
+                ctx.restore_kv_layers(l0, hidden_dev[l0:l0 + G], d_pos, T, d_bt, len(bt), use[i % len(use)])
+            return
         for l in range(L):
             if ragged:
                 ctx.restore_kv_ragged(l, hidden_dev[l], d_pos, T, d_cu, w.n_seq, d_bt, bt.shape[1],
@@ -209,13 +225,17 @@ def main():
     for _ in range(max(1, min(args.steps, 4096 // L))):
         step([stream])                                      # one stream: kernels back to back
     avg_ms, launches = ctx.timing_end(stream)
-    flop_per_launch = 4.0 * T * d * w.d_kv               # 2 flop per multiply-add, K and V
+    layers_per_launch = L / launches * max(1, min(args.steps, 4096 // L))
+    flop_per_launch = 4.0 * T * d * w.d_kv * layers_per_launch   # 2 flop per multiply-add, K and V
     achieved = flop_per_launch / (avg_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "restore_kernel", "achieved": round(achieved, 2),
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
-                "traffic": None if args.zero_inputs else TRAFFIC_BYTES_PER_LAUNCH.get(w.name),
+                "traffic": None if args.zero_inputs or w.name not in TRAFFIC_BYTES_PER_LAUNCH
+                else (TRAFFIC_BYTES_PER_LAUNCH[w.name] if layers_per_launch == 1
+                      else TRAFFIC_BYTES_PER_LAYER_FUSED[w.name] * layers_per_launch),
                 "avg_launch_us": round(avg_ms * 1e3, 2), "launches_timed": launches,
+                "layers_per_launch": round(layers_per_launch, 2),
                 "flop_per_launch": flop_per_launch}
     assert ctx.poll_device_error(stream) == 0
 
@@ -278,7 +298,8 @@ def main():
         "data": "synthetic" if not args.zero_inputs else "zeros (diagnostic)",
         "config": {"workload": w.name, "layers": L, "d_model": d, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "tokens": T, "block_size": w.block_size,
-                   "hidden_resident_in_hbm": True, "launch_streams": args.streams},
+                   "hidden_resident_in_hbm": True, "launch_streams": args.streams,
+                   "layers_per_launch": G},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "e2e_host_link": e2e,

@@ -142,6 +142,18 @@ hc_status hc_restore_kv(hc_ctx* ctx, int32_t layer, const void* d_hidden,
                         const int32_t* d_positions, int32_t n_tok,
                         const int32_t* d_block_table, int32_t n_blocks, void* stream);
 
+/* The same for layers [layer_begin, layer_begin + n_layers) of one context whose saved inputs
+ * are ALL resident in HBM: h_d_hidden is a HOST array of n_layers device pointers, entry i =
+ * bf16 [n_tok, d_model] of layer layer_begin + i; positions and block table are shared (one
+ * context).  The layers go out in as few launches as possible (up to 32 layers each), which
+ * removes the gaps between per-layer kernels and lets the compute units run out of step.
+ * Per layer the result is identical to hc_restore_kv's.  Every layer needs weights and a
+ * pool (HC_ESTATE).  The pointer array is read during the call only. */
+hc_status hc_restore_kv_layers(hc_ctx* ctx, int32_t layer_begin, int32_t n_layers,
+                               const void* const* h_d_hidden, const int32_t* d_positions,
+                               int32_t n_tok, const int32_t* d_block_table, int32_t n_blocks,
+                               void* stream);
+
 /* Ragged batch: the tokens of n_seq contexts concatenated into one projection.
  *   d_cu_seqlens   int32 [n_seq + 1]          context s owns rows cu[s] .. cu[s+1]-1
  *   d_block_tables int32 [n_seq][max_blocks]  one row per context, padded with -1
@@ -318,7 +330,8 @@ hc_status hc_partition_layers(int32_t n_layers, double io_h, double io_kv, doubl
 hc_status hc_set_loader(hc_ctx* ctx, int32_t mode);
 
 /* ---- measurement hooks -------------------------------------------------------------
- * Average duration in milliseconds of the restoration kernel launches queued on
+ * Average duration in milliseconds of the restoration kernel launches (one per layer, or
+ * one per group of layers under hc_restore_kv_layers) queued on
  * `stream` between hc_timing_begin and hc_timing_end, measured with HIP events on that
  * stream around every launch of this context (at most 4096 launches are recorded).
  * hc_timing_end synchronises the stream.  *out_launches receives the launch count. */

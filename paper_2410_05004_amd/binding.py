@@ -58,6 +58,7 @@ def _load():
         "hc_set_layer_weights_affine": (i32, [vp, i32, vp, vp, vp, vp, vp]),
         "hc_set_kv_pool": (i32, [vp, i32, vp, i64]),
         "hc_restore_kv": (i32, [vp, i32, vp, vp, i32, vp, i32, vp]),
+        "hc_restore_kv_layers": (i32, [vp, i32, i32, p(vp), vp, i32, vp, i32, vp]),
         "hc_restore_kv_ragged": (i32, [vp, i32, vp, vp, i32, vp, i32, vp, i32, vp]),
         "hc_poll_device_error": (i32, [vp, vp, p(i32)]),
         "hc_store_create": (i32, [i32, i32, i32, i64, p(vp)]),
@@ -98,7 +99,7 @@ EXPORTED = ("hc_last_error hc_version hc_validate_desc hc_create hc_destroy hc_s
             "hc_saver_create hc_saver_destroy hc_saver_save_layer hc_saver_save_layer_host "
             "hc_saver_flush hc_partition_layers hc_gather_kv hc_scatter_kv "
             "hc_restore_context_mixed hc_set_layer_weights_affine hc_saver_save_layer_deferred "
-            "hc_saver_fence").split()
+            "hc_saver_fence hc_restore_kv_layers").split()
 
 
 def _check(status):
@@ -167,6 +168,14 @@ class Context:
     def restore_kv(self, layer, d_hidden, d_positions, n_tok, d_block_table, n_blocks, stream=0):
         _check(lib.hc_restore_kv(self._h, layer, _ptr(d_hidden), _ptr(d_positions), n_tok,
                                  _ptr(d_block_table), n_blocks, stream))
+
+    def restore_kv_layers(self, layer_begin, d_hidden_list, d_positions, n_tok, d_block_table,
+                          n_blocks, stream=0):
+        """d_hidden_list: one device tensor (or address) per layer, starting at layer_begin."""
+        n = len(d_hidden_list)
+        arr = (C.c_void_p * max(n, 1))(*[_ptr(h) for h in d_hidden_list])
+        _check(lib.hc_restore_kv_layers(self._h, layer_begin, n, arr, _ptr(d_positions), n_tok,
+                                        _ptr(d_block_table), n_blocks, stream))
 
     def restore_kv_ragged(self, layer, d_hidden, d_positions, total_tokens, d_cu_seqlens, n_seq,
                           d_block_tables, max_blocks, stream=0):

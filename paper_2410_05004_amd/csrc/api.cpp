@@ -53,26 +53,16 @@ static hc_status check_layer(const hc_ctx* ctx, int32_t layer) {
   return HC_OK;
 }
 
-// Launch the fused kernel for one layer (shared by the three restore entry points).
-hc_status restore_layer(hc_ctx* ctx, int32_t layer, const void* d_hidden,
-                        const int32_t* d_positions, int32_t pos_base, int32_t n_tok,
-                        const int32_t* d_cu, int32_t n_seq, const int32_t* d_tables,
-                        int32_t max_blocks, hipStream_t stream) {
-  const hc_layer_state& L = ctx->layers[layer];
-  if (!L.wpack) return fail(HC_ESTATE, "hc_set_layer_weights was not called for this layer");
-  if (!L.pool) return fail(HC_ESTATE, "hc_set_kv_pool was not called for this layer");
-  RestoreArgs a;
-  a.hidden = static_cast<const uint16_t*>(d_hidden);
-  a.wpack = L.wpack;
+// Arguments shared by all layers of a context's launch.
+static RestoreArgs shared_args(const hc_ctx* ctx, const int32_t* d_positions, int32_t pos_base,
+                               int32_t n_tok, const int32_t* d_cu, int32_t n_seq,
+                               const int32_t* d_tables, int32_t max_blocks) {
+  RestoreArgs a{};
   a.positions = d_positions;
   a.cu_seqlens = d_cu;
   a.block_tables = d_tables;
   a.rope = ctx->rope;
-  a.affine = L.affine;
-  a.mode = ctx->desc.norm_kind == HC_NORM_LAYER ? 2 : (L.affine ? 1 : 0);
-  a.pool = L.pool;
   a.err = ctx->err_dev;
-  a.num_pages = L.num_pages;
   a.pos_base = pos_base;
   a.n_seq = n_seq;
   a.max_blocks = max_blocks;
@@ -86,7 +76,16 @@ hc_status restore_layer(hc_ctx* ctx, int32_t layer, const void* d_hidden,
   a.rope_style = ctx->desc.rope_style;
   a.inv_d = 1.0f / (float)ctx->desc.d_model;
   a.eps = ctx->desc.rms_eps;
+  return a;
+}
 
+static int layer_mode(const hc_ctx* ctx, const hc_layer_state& L) {
+  return ctx->desc.norm_kind == HC_NORM_LAYER ? 2 : (L.affine ? 1 : 0);
+}
+
+// One timed (when timing is on) launch.
+static hc_status timed_launch(hc_ctx* ctx, const RestoreArgs& a, LayerBatch* batch, int n_layers,
+                              hipStream_t stream) {
   const bool timed = ctx->timing && ctx->ev_used + 2 <= 8192;
   if (timed) {
     while ((int)ctx->ev_pool.size() < ctx->ev_used + 2) {
@@ -96,10 +95,61 @@ hc_status restore_layer(hc_ctx* ctx, int32_t layer, const void* d_hidden,
     }
     HC_HIP(hipEventRecord(ctx->ev_pool[ctx->ev_used], stream));
   }
-  HC_HIP(launch_restore(a, stream));
+  HC_HIP(launch_restore(a, batch, n_layers, stream));
   if (timed) {
     HC_HIP(hipEventRecord(ctx->ev_pool[ctx->ev_used + 1], stream));
     ctx->ev_used += 2;
+  }
+  return HC_OK;
+}
+
+// Launch the fused kernel for one layer (shared by the single-layer restore entry points).
+hc_status restore_layer(hc_ctx* ctx, int32_t layer, const void* d_hidden,
+                        const int32_t* d_positions, int32_t pos_base, int32_t n_tok,
+                        const int32_t* d_cu, int32_t n_seq, const int32_t* d_tables,
+                        int32_t max_blocks, hipStream_t stream) {
+  const hc_layer_state& L = ctx->layers[layer];
+  if (!L.wpack) return fail(HC_ESTATE, "hc_set_layer_weights was not called for this layer");
+  if (!L.pool) return fail(HC_ESTATE, "hc_set_kv_pool was not called for this layer");
+  RestoreArgs a = shared_args(ctx, d_positions, pos_base, n_tok, d_cu, n_seq, d_tables, max_blocks);
+  a.hidden = static_cast<const uint16_t*>(d_hidden);
+  a.wpack = L.wpack;
+  a.affine = L.affine;
+  a.mode = layer_mode(ctx, L);
+  a.pool = L.pool;
+  a.num_pages = L.num_pages;
+  return timed_launch(ctx, a, nullptr, 1, stream);
+}
+
+hc_status restore_layers(hc_ctx* ctx, int32_t layer_begin, int32_t n_layers,
+                         const void* const* d_hidden, const int32_t* d_positions, int32_t pos_base,
+                         int32_t n_tok, const int32_t* d_block_table, int32_t n_blocks,
+                         hipStream_t stream) {
+  for (int i = 0; i < n_layers; ++i) {
+    const hc_layer_state& L = ctx->layers[layer_begin + i];
+    if (!L.wpack) return fail(HC_ESTATE, "hc_set_layer_weights was not called for some layer");
+    if (!L.pool) return fail(HC_ESTATE, "hc_set_kv_pool was not called for some layer");
+    if (!d_hidden[i]) return fail(HC_EINVAL, "null hidden-state pointer");
+    if (!aligned16(d_hidden[i])) return fail(HC_EALIGN, "hidden not 16-byte aligned");
+  }
+  RestoreArgs a = shared_args(ctx, d_positions, pos_base, n_tok, nullptr, 1, d_block_table, n_blocks);
+  int i = 0;
+  while (i < n_layers) {
+    // one launch per run of layers with the same kernel mode, at most kMaxLayersPerLaunch
+    LayerBatch batch{};
+    const int mode = layer_mode(ctx, ctx->layers[layer_begin + i]);
+    int n = 0;
+    while (i + n < n_layers && n < kMaxLayersPerLaunch &&
+           layer_mode(ctx, ctx->layers[layer_begin + i + n]) == mode) {
+      const hc_layer_state& L = ctx->layers[layer_begin + i + n];
+      batch.e[n] = LayerEntry{static_cast<const uint16_t*>(d_hidden[i + n]), L.wpack, L.affine, L.pool,
+                              L.num_pages};
+      ++n;
+    }
+    a.mode = mode;
+    hc_status r = timed_launch(ctx, a, &batch, n, stream);
+    if (r != HC_OK) return r;
+    i += n;
   }
   return HC_OK;
 }
@@ -280,6 +330,21 @@ hc_status hc_restore_kv(hc_ctx* ctx, int32_t layer, const void* d_hidden,
   if (!aligned16(d_hidden)) return fail(HC_EALIGN, "hidden not 16-byte aligned");
   return restore_layer(ctx, layer, d_hidden, d_positions, 0, n_tok, nullptr, 1, d_block_table,
                        n_blocks, static_cast<hipStream_t>(stream));
+}
+
+hc_status hc_restore_kv_layers(hc_ctx* ctx, int32_t layer_begin, int32_t n_layers,
+                               const void* const* h_d_hidden, const int32_t* d_positions,
+                               int32_t n_tok, const int32_t* d_block_table, int32_t n_blocks,
+                               void* stream) {
+  clear_error();
+  if (!ctx) return fail(HC_EINVAL, "ctx is null");
+  if (n_layers < 0 || n_tok < 0 || n_blocks < 0) return fail(HC_EINVAL, "negative size");
+  if (layer_begin < 0 || (int64_t)layer_begin + n_layers > ctx->desc.n_layers)
+    return fail(HC_ERANGE, "layer range outside the model");
+  if (n_layers == 0 || n_tok == 0) return HC_OK;
+  if (!h_d_hidden || !d_positions || !d_block_table) return fail(HC_EINVAL, "null pointer");
+  return restore_layers(ctx, layer_begin, n_layers, h_d_hidden, d_positions, 0, n_tok, d_block_table,
+                        n_blocks, static_cast<hipStream_t>(stream));
 }
 
 hc_status hc_restore_kv_ragged(hc_ctx* ctx, int32_t layer, const void* d_hidden,

@@ -61,8 +61,25 @@ struct RestoreArgs {
   float eps;
 };
 
+// Per-layer pointers of a launch that covers several layers of one context (the shared
+// fields of RestoreArgs apply to all of them; its hidden / wpack / affine / pool / num_pages
+// are ignored).  Passed by value as a kernel argument.
+struct LayerEntry {
+  const uint16_t* hidden;
+  const uint16_t* wpack;
+  const float2* affine;
+  uint16_t* pool;
+  int64_t num_pages;
+};
+constexpr int kMaxLayersPerLaunch = 32;
+struct LayerBatch {
+  LayerEntry e[kMaxLayersPerLaunch];
+  int32_t slots_per_layer;     // workgroups per layer (a multiple of 8); set by launch_restore
+};
+
 // Launchers implemented in the .hip files.  All are asynchronous on `stream`.
-hipError_t launch_restore(const RestoreArgs& a, hipStream_t stream);
+// `batch` null: one layer from `a`; else n_layers <= kMaxLayersPerLaunch layers in one launch.
+hipError_t launch_restore(const RestoreArgs& a, LayerBatch* batch, int n_layers, hipStream_t stream);
 hipError_t launch_pack_weights(const uint16_t* wkv, const uint16_t* gamma, uint16_t* wpack,
                                int d_model, int d_kv, int head_dim, int rope_style,
                                hipStream_t stream);
@@ -120,6 +137,13 @@ hc_status restore_layer(hc_ctx* ctx, int32_t layer, const void* d_hidden,
                         const int32_t* d_positions, int32_t pos_base, int32_t n_tok,
                         const int32_t* d_cu, int32_t n_seq, const int32_t* d_tables,
                         int32_t max_blocks, hipStream_t stream);
+// The same for layers [layer_begin, layer_begin + n_layers) of one context, hidden states of
+// layer layer_begin + i at d_hidden[i] (host array of device pointers); as few launches as
+// kMaxLayersPerLaunch and equal kernel modes allow.
+hc_status restore_layers(hc_ctx* ctx, int32_t layer_begin, int32_t n_layers,
+                         const void* const* d_hidden, const int32_t* d_positions, int32_t pos_base,
+                         int32_t n_tok, const int32_t* d_block_table, int32_t n_blocks,
+                         hipStream_t stream);
 // Validated launch of the KV row copy for one layer: rows -> pages (to_pool) or pages -> rows.
 hc_status kv_rows_layer(hc_ctx* ctx, int32_t layer, void* d_rows, const int32_t* d_positions,
                         int32_t pos_base, int32_t n_tok, const int32_t* d_block_table,

@@ -4,8 +4,9 @@
 
 namespace hc {
 
-hipError_t launch_mode0(const RestoreArgs& a, const TileGrid& g, unsigned grid, hipStream_t stream) {
-  return launch_mode<0>(a, g, grid, stream);
+hipError_t launch_mode0(const RestoreArgs& a, const TileGrid& g, unsigned grid, const LayerBatch* mb,
+                        hipStream_t stream) {
+  return launch_mode<0>(a, g, grid, mb, stream);
 }
 hipError_t configure_mode0() { return configure_mode<0>(); }
 
@@ -17,7 +18,7 @@ hipError_t configure_kernels() {
   return configure_mode2();
 }
 
-hipError_t launch_restore(const RestoreArgs& a, hipStream_t stream) {
+hipError_t launch_restore(const RestoreArgs& a, LayerBatch* batch, int n_layers, hipStream_t stream) {
   if (a.n_tok <= 0) return hipSuccess;
   TileGrid g;
   g.nf = 2 * a.d_kv_pad / kTileF;
@@ -41,10 +42,14 @@ hipError_t launch_restore(const RestoreArgs& a, hipStream_t stream) {
     }
   }
   g.nsf = (g.nf + (1 << g.gf_shift) - 1) >> g.gf_shift;
-  const unsigned grid = (unsigned)best_slots * 8u;
-  if (a.mode == 0) return launch_mode0(a, g, grid, stream);
-  if (a.mode == 1) return launch_mode1(a, g, grid, stream);
-  return launch_mode2(a, g, grid, stream);
+  unsigned grid = (unsigned)best_slots * 8u;
+  if (batch) {
+    batch->slots_per_layer = (int32_t)grid;
+    grid *= (unsigned)n_layers;
+  }
+  if (a.mode == 0) return launch_mode0(a, g, grid, batch, stream);
+  if (a.mode == 1) return launch_mode1(a, g, grid, batch, stream);
+  return launch_mode2(a, g, grid, batch, stream);
 }
 
 }  // namespace hc

@@ -3,8 +3,9 @@
 
 namespace hc {
 
-hipError_t launch_mode1(const RestoreArgs& a, const TileGrid& g, unsigned grid, hipStream_t stream) {
-  return launch_mode<1>(a, g, grid, stream);
+hipError_t launch_mode1(const RestoreArgs& a, const TileGrid& g, unsigned grid, const LayerBatch* mb,
+                        hipStream_t stream) {
+  return launch_mode<1>(a, g, grid, mb, stream);
 }
 hipError_t configure_mode1() { return configure_mode<1>(); }
 

@@ -132,3 +132,79 @@ def test_opt30b_shape(hc):
               flush=True)
         del pool
     ctx.destroy()
+
+
+@pytest.mark.parametrize("norm_kind", [0, 1])
+def test_layers_in_one_launch(hc, norm_kind):
+    """hc_restore_kv_layers over 35 layers (more than one launch holds; layers with and without
+    a bias, so the kernel mode changes along the way) writes bit for bit what one
+    hc_restore_kv per layer writes, and that is the oracle's result."""
+    import torch
+    rng = np.random.default_rng([9, norm_kind])
+    L, d_model, n_kv, hd, B, T = 35, 256, 2, 64, 16, 300
+    d_kv = n_kv * hd
+    n_blocks = 24
+    num_pages = n_blocks + 4
+    desc = gh.make_desc(hc, n_layers=L, d_model=d_model, n_q_heads=n_kv, n_kv_heads=n_kv, head_dim=hd,
+                        block_size=B, max_position=n_blocks * B, norm_kind=norm_kind)
+    ctx = hc.Context(desc)
+    s = gh.stream_handle()
+    pos = rng.permutation(n_blocks * B)[:T].astype(np.int32)
+    bt = rng.permutation(num_pages)[:n_blocks].astype(np.int32)
+    d_pos, d_bt = gh.to_dev_i32(pos), gh.to_dev_i32(bt)
+    f = syn.bf16_bits_to_f64
+    hidden, pools_a, pools_b, params, keep = [], [], [], [], []
+    for l in range(L):
+        wkv, gamma = bf16(rng, (2 * d_kv, d_model), 0, 0.02), bf16(rng, (d_model,), 1, 0.1)
+        bias = bf16(rng, (2 * d_kv,), 0, 0.05) if l % 5 in (1, 2) else None
+        beta = bf16(rng, (d_model,), 0, 0.05) if norm_kind == 1 and l % 3 == 0 else None
+        x = bf16(rng, (T, d_model), 0.3, 1.0)
+        params.append((wkv, gamma, beta, bias, x))
+        dev = [gh.to_dev_bf16(a) if a is not None else None for a in (wkv, gamma, beta, bias)]
+        keep.append(dev)
+        if beta is not None or bias is not None:
+            ctx.set_layer_weights_affine(l, dev[0], dev[1], dev[2], dev[3], s)
+        else:
+            ctx.set_layer_weights(l, dev[0], dev[1], s)
+        hidden.append(gh.to_dev_bf16(x))
+        pools_a.append(gh.new_pool(num_pages, B, n_kv, hd))
+        pools_b.append(gh.new_pool(num_pages, B, n_kv, hd))
+    for l in range(L):
+        ctx.set_kv_pool(l, pools_a[l], num_pages)
+        ctx.restore_kv(l, hidden[l], d_pos, T, d_bt, n_blocks, s)
+    for l in range(L):
+        ctx.set_kv_pool(l, pools_b[l], num_pages)
+    ctx.timing_begin()
+    ctx.restore_kv_layers(0, hidden, d_pos, T, d_bt, n_blocks, s)
+    _, launches = ctx.timing_end(s)
+    assert ctx.poll_device_error(s) == 0
+    if norm_kind == 1:
+        assert launches == 2                              # one mode: 32 + 3 layers
+    else:
+        assert launches > 2                               # the mode changes with the bias
+    for l in (0, 1, 2, 3, 17, 31, 32, 34):
+        a, b = gh.pool_bits(pools_a[l]), gh.pool_bits(pools_b[l])
+        assert np.array_equal(a, b), f"layer {l}: fused launch differs from the single-layer launch"
+        wkv, gamma, beta, bias, x = params[l]
+        ora = np.full((num_pages, 2, B, n_kv, hd), np.nan)
+        oracle.restore_kv(ora, f(x), f(gamma), f(wkv), pos, bt, beta=None if beta is None else f(beta),
+                          bias=None if bias is None else f(bias), **gh.oracle_kw(desc))
+        gh.compare_pool(b, ora)
+    # a sub-range, and argument errors
+    pools_c = [gh.new_pool(num_pages, B, n_kv, hd) for _ in range(3)]
+    for i in range(3):
+        ctx.set_kv_pool(10 + i, pools_c[i], num_pages)
+    ctx.restore_kv_layers(10, hidden[10:13], d_pos, T, d_bt, n_blocks, s)
+    for i in range(3):
+        assert np.array_equal(gh.pool_bits(pools_c[i]), gh.pool_bits(pools_a[10 + i]))
+    for args, st in [((30, hidden[:6], d_pos, T, d_bt, n_blocks, s), hc.HC_ERANGE),
+                     ((-1, hidden[:2], d_pos, T, d_bt, n_blocks, s), hc.HC_ERANGE),
+                     ((0, [hidden[0], None], d_pos, T, d_bt, n_blocks, s), hc.HC_EINVAL),
+                     ((0, [hidden[0].data_ptr() + 2], d_pos, T, d_bt, n_blocks, s), hc.HC_EALIGN),
+                     ((0, hidden[:2], None, T, d_bt, n_blocks, s), hc.HC_EINVAL)]:
+        with pytest.raises(hc.HCacheError) as e:
+            ctx.restore_kv_layers(*args)
+        assert e.value.status == st
+    ctx.restore_kv_layers(0, [], d_pos, T, d_bt, n_blocks, s)          # nothing to do
+    torch.cuda.synchronize()
+    ctx.destroy()
