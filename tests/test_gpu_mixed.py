@@ -205,3 +205,72 @@ def test_restore_context_mixed(hc, torch, l_h):
     for st in (hstore, kstore):
         if st is not None:
             st.destroy()
+
+
+def test_mixed_restore_at_7b_width(hc, torch):
+    """The paper's schedule for Llama-2-7B is 31 layers from hidden states + 1 from KV offload
+    (Table 3).  Full width (d_model 4096, 32 KV heads), 2048 tokens, streamed from pinned
+    stores in 256-token chunks; three layers stand for the 32 (two projected, one offloaded):
+    whole-pool indexing, sampled rows and a random projection for the projected layers, every
+    byte for the offloaded one."""
+    import synthetic as syn
+    from test_gpu_fullsize import check_layer, sample_rows
+    w = syn.WORKLOADS[1]
+    T, B, CT = w.tokens, w.block_size, w.chunk_tokens
+    model_layers = (0, 30, 31)                           # the last one comes from KV rows
+    L, l_h = len(model_layers), 2
+    desc = gh.make_desc(hc, n_layers=L, d_model=w.d_model, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads,
+                        head_dim=w.head_dim, block_size=B, max_position=T, rope_theta=w.rope_theta,
+                        rms_eps=w.rms_eps)
+    ctx = hc.Context(desc)
+    s = gh.stream_handle()
+    copy_stream = torch.cuda.Stream()
+    bt_gen, num_pages = syn.block_table(w, T, seq=1)
+    bt, _ = syn.block_table(w, T, seq=0)
+    d_bt_gen, d_bt = gh.to_dev_i32(bt_gen), gh.to_dev_i32(bt)
+    pos = np.arange(T, dtype=np.int32)
+    d_pos = gh.to_dev_i32(pos)
+    data = []
+    for i, l in enumerate(model_layers):
+        wkv, gamma = syn.layer_weights(w, l)
+        x = syn.layer_hidden(w, l)
+        data.append((wkv, gamma, x))
+        ctx.set_layer_weights(i, gh.to_dev_bf16(wkv), gh.to_dev_bf16(gamma), s)
+        torch.cuda.synchronize()
+    # generation time: the offloaded layer's KV exists in a cache under another block table
+    gen_pool = gh.new_pool(num_pages, B, w.n_kv_heads, w.head_dim)
+    ctx.set_kv_pool(2, gen_pool, num_pages)
+    ctx.restore_kv(2, gh.to_dev_bf16(data[2][2]), d_pos, T, d_bt_gen, len(bt_gen), s)
+    rows_dev = torch.zeros((T, 2 * w.d_kv), dtype=torch.bfloat16, device="cuda")
+    ctx.gather_kv(2, rows_dev, d_pos, T, d_bt_gen, len(bt_gen), s)
+    kv_rows = rows_dev.view(torch.int16).cpu().numpy().view(np.uint16)
+    n_chunks = T // CT
+    hstore = hc.Store(l_h, w.d_model, CT, l_h * n_chunks)
+    kstore = hc.Store(1, 2 * w.d_kv, CT, n_chunks)
+    for c in range(n_chunks):                            # arrival order: chunk by chunk, layer by layer
+        for i in range(l_h):
+            hstore.append(5, i, np.ascontiguousarray(data[i][2][c * CT:(c + 1) * CT]), CT)
+        kstore.append(5, 0, np.ascontiguousarray(kv_rows[c * CT:(c + 1) * CT]), CT)
+    pools = [gh.new_pool(num_pages, B, w.n_kv_heads, w.head_dim) for _ in range(L)]
+    for i in range(L):
+        ctx.set_kv_pool(i, pools[i], num_pages)
+    ctx.restore_context_mixed(hstore, kstore, l_h, 5, 0, T, 0, d_bt, len(bt), s, copy_stream.cuda_stream)
+    assert ctx.poll_device_error(s) == 0
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(77)
+    rows = sample_rows(rng, T, [256 * i for i in range(1, T // 256)], range(B), range(T - B, T), 256)
+    for i in range(l_h):
+        res = check_layer(w, desc, gh.pool_bits(pools[i]), data[i][2], data[i][0], data[i][1], pos,
+                          np.zeros(T, dtype=np.int64), bt[None, :], rows, rng)
+        print(f"layer {model_layers[i]} (from hidden states): sampled {res[0]:.4f} x RMS", flush=True)
+    want = np.full((num_pages, 2, B, w.n_kv_heads, w.head_dim), gh.SENTINEL, dtype=np.uint16)
+    oracle.scatter_kv(want, kv_rows[:, :w.d_kv].reshape(T, w.n_kv_heads, w.head_dim),
+                      kv_rows[:, w.d_kv:].reshape(T, w.n_kv_heads, w.head_dim), pos, bt, B)
+    assert np.array_equal(gh.pool_bits(pools[2]), want)
+    # and those bytes are what projecting the layer's hidden states gives
+    res = check_layer(w, desc, gh.pool_bits(pools[2]), data[2][2], data[2][0], data[2][1], pos,
+                      np.zeros(T, dtype=np.int64), bt[None, :], rows, rng)
+    print(f"layer 31 (from KV rows): sampled {res[0]:.4f} x RMS", flush=True)
+    ctx.destroy()
+    hstore.destroy()
+    kstore.destroy()

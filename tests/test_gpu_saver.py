@@ -113,3 +113,44 @@ def test_saver_argument_errors(hc):
     assert store.tokens(0, 0) == 16
     saver.destroy()
     store.destroy()
+
+
+def test_saver_at_13b_width(hc):
+    """Batches of the size the paper quotes for a 13B model (1024-row prefill chunks of
+    d_model 5120, then 48-context decode steps) through the deferred-fence save path; the
+    store must hold exactly what the oracle's model of the two stages holds."""
+    import torch
+    L, d_model, CT = 3, 5120, 64
+    rng = np.random.default_rng(13)
+    n_ctx, prefill, decode_steps = 48, 1024, 5
+    store = hc.Store(L, d_model, CT, L * ((prefill + CT - 1) // CT + n_ctx) + n_ctx * L + 8, pinned=True)
+    saver = hc.Saver(store, 1024, n_slots=4, n_threads=8)
+    ref = oracle.ChunkStore(L, d_model, CT)
+    compute = torch.cuda.current_stream()
+    down = torch.cuda.Stream()
+    act = torch.empty((1024, d_model), dtype=torch.bfloat16, device="cuda")
+
+    def save_step(row_seq, bits_per_layer):
+        n = len(row_seq)
+        for l in range(L):
+            act[:n].copy_(gh.to_dev_bf16(bits_per_layer[l]))
+            saver.save_layer_deferred(l, act, n, row_seq, compute.cuda_stream, down.cuda_stream)
+            saver.fence(compute.cuda_stream)
+            act.fill_(0.5)
+            oracle.save_step(ref, l, bits_per_layer[l], row_seq)
+
+    # context 100: one 1024-row prefill chunk
+    save_step(np.full(prefill, 100, dtype=np.int64),
+              [rng.integers(0, 1 << 16, size=(prefill, d_model), dtype=np.uint16) for _ in range(L)])
+    # 48 contexts decode together (context 100 among them)
+    ids = np.array([100] + list(range(1, n_ctx)), dtype=np.int64)
+    for _ in range(decode_steps):
+        save_step(ids, [rng.integers(0, 1 << 16, size=(n_ctx, d_model), dtype=np.uint16) for _ in range(L)])
+    saver.flush()
+    for sid in (100, 1, n_ctx - 1):
+        for l in range(L):
+            assert store.tokens(sid, l) == ref.n_tokens(sid, l)
+            for c in range(ref.n_chunks(sid, l)):
+                assert np.array_equal(read_chunk(store, sid, l, c, d_model), ref.chunk(sid, l, c)), (sid, l, c)
+    saver.destroy()
+    store.destroy()
