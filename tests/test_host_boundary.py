@@ -168,3 +168,23 @@ def test_bench_refuses_more_than_one_gpu():
     assert res.returncode != 0
     assert "one GPU" in res.stderr
     assert res.stdout.strip() == ""
+
+
+def test_header_is_plain_c_and_links(hc, tmp_path):
+    """include/hcache.h compiles as pedantic C99 and a C program can call the library."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    libdir = os.path.dirname(hc.lib_path())
+    exe = str(tmp_path / "cabi_smoke")
+    rocm_lib = "/opt/rocm/lib"
+    cmd = [gcc, "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "cabi_smoke.c"), "-o", exe, "-L", libdir, "-lhcache",
+           f"-Wl,-rpath,{libdir}", f"-Wl,-rpath,{rocm_lib}"]
+    res = subprocess.run(cmd, capture_output=True, text=True, timeout=120)
+    assert res.returncode == 0, res.stderr
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+    assert res.returncode == 0, (res.returncode, res.stdout, res.stderr)
+    assert "hcache-mi355x" in res.stdout
