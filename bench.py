@@ -91,6 +91,8 @@ def main():
                     help="layers restored by one kernel launch (hidden states of all layers are resident "
                          "in HBM here, so they can go out together: hc_restore_kv_layers); 1 = one launch "
                          "per layer (hc_restore_kv), as the pipelined loader issues them")
+    ap.add_argument("--rope-style", type=int, default=None,
+                    help="override the workload's RoPE convention (0 half-split, 1 interleaved, 2 none)")
     ap.add_argument("--loader", type=int, default=0, help="0 = copy engines, strided runs (default), 1 = gather kernel")
     ap.add_argument("--zero-inputs", action="store_true",
                     help="diagnostic: all-zero hidden states and weights (same instruction stream, no "
@@ -124,7 +126,8 @@ def main():
     log(f"workload {w.name}: L={L} d={d} d_kv={w.d_kv} T={T}")
 
     desc = hc.ModelDesc(L, d, w.n_q_heads, w.n_kv_heads, w.head_dim, w.block_size,
-                        max_pos, w.rope_style, w.rope_theta, w.rms_eps,
+                        max_pos, w.rope_style if args.rope_style is None else args.rope_style,
+                        w.rope_theta, w.rms_eps,
                         hc.HC_NORM_LAYER if w.norm == "layer" else hc.HC_NORM_RMS)
     ctx = hc.Context(desc)
     stream = torch.cuda.current_stream().cuda_stream
