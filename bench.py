@@ -3,7 +3,7 @@
 
 A step = one restoration of the whole workload: for every layer, the fused kernel
 (RMSNorm -> K|V projection -> RoPE -> paged scatter) over all tokens, hidden states
-already resident in HBM; the layers of a step go out in one launch per 32 layers.  `value` is restored tokens per second over all layers.
+already resident in HBM; the layers of a step go out eight per launch.  `value` is restored tokens per second over all layers.
 The same JSON line carries the roofline of the dominant kernel (measured with HIP
 events around every launch), the fp64 oracle timed on the host cores on a bounded
 sample, and the PCIe-inclusive end-to-end figure (chunk store -> H2D -> kernel,
@@ -30,9 +30,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16, vendor figure without s
 # profiles/restore_kernel_llama3-8b-gqa-T8192.md.  Bytes per layer (a launch over several layers
 # moves that many times as much); None where not profiled.
 TRAFFIC_BYTES_PER_LAUNCH = {"llama3-8b-gqa-T8192": 2.436e8}
-# the same per layer inside a launch over 32 layers (the compute units run out of step and share
-# less in the per-XCD L2)
-TRAFFIC_BYTES_PER_LAYER_FUSED = {"llama3-8b-gqa-T8192": 3.213e8}
+# the same per layer inside a launch over 8 layers (fetched 200.4 MiB + written 32.03 MiB)
+TRAFFIC_BYTES_PER_LAYER_FUSED = {"llama3-8b-gqa-T8192": 2.437e8}
 
 
 def log(*a):
@@ -89,8 +88,9 @@ def main():
                     help="streams the per-layer launches of a step are dealt over (layers are independent)")
     ap.add_argument("--layers-per-launch", type=int, default=32,
                     help="layers restored by one kernel launch (hidden states of all layers are resident "
-                         "in HBM here, so they can go out together: hc_restore_kv_layers); 1 = one launch "
-                         "per layer (hc_restore_kv), as the pipelined loader issues them")
+                         "in HBM here, so they can go out together: hc_restore_kv_layers, which launches "
+                         "them eight at a time); 1 = one launch per layer (hc_restore_kv), as the pipelined "
+                         "loader issues them")
     ap.add_argument("--rope-style", type=int, default=None,
                     help="override the workload's RoPE convention (0 half-split, 1 interleaved, 2 none)")
     ap.add_argument("--loader", type=int, default=0, help="0 = copy engines, strided runs (default), 1 = gather kernel")

@@ -145,7 +145,7 @@ hc_status hc_restore_kv(hc_ctx* ctx, int32_t layer, const void* d_hidden,
 /* The same for layers [layer_begin, layer_begin + n_layers) of one context whose saved inputs
  * are ALL resident in HBM: h_d_hidden is a HOST array of n_layers device pointers, entry i =
  * bf16 [n_tok, d_model] of layer layer_begin + i; positions and block table are shared (one
- * context).  The layers go out in as few launches as possible (up to 32 layers each), which
+ * context).  The layers go out in launches of up to 8 layers each, which
  * removes the gaps between per-layer kernels and lets the compute units run out of step.
  * Per layer the result is identical to hc_restore_kv's.  Every layer needs weights and a
  * pool (HC_ESTATE).  The pointer array is read during the call only. */

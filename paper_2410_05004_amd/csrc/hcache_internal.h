@@ -71,7 +71,10 @@ struct LayerEntry {
   uint16_t* pool;
   int64_t num_pages;
 };
-constexpr int kMaxLayersPerLaunch = 32;
+// 8 layers per launch: enough rounds of workgroups to hide the gaps between kernels, few
+// enough that the CUs of an XCD stay close together and keep sharing weights in its L2
+// (measured: 16 and 32 layers per launch fetch 4 % and 37 % more, and are no faster)
+constexpr int kMaxLayersPerLaunch = 8;
 struct LayerBatch {
   LayerEntry e[kMaxLayersPerLaunch];
   int32_t slots_per_layer;     // workgroups per layer (a multiple of 8); set by launch_restore
