@@ -208,3 +208,77 @@ def test_layers_in_one_launch(hc, norm_kind):
     ctx.restore_kv_layers(0, [], d_pos, T, d_bt, n_blocks, s)          # nothing to do
     torch.cuda.synchronize()
     ctx.destroy()
+
+
+def test_opt_style_ragged_and_streamed(hc):
+    """OPT-style layers through the other entry points: a ragged batch of four contexts in one
+    launch, and a whole-context pipelined restore from the chunk store."""
+    import torch
+    rng = np.random.default_rng(21)
+    L, d_model, n_kv, hd, B, CT = 2, 1024, 4, 128, 16, 64
+    d_kv = n_kv * hd
+    desc = gh.make_desc(hc, n_layers=L, d_model=d_model, n_q_heads=n_kv, n_kv_heads=n_kv, head_dim=hd,
+                        block_size=B, max_position=1024, rope_style=2, norm_kind=1)
+    ctx = hc.Context(desc)
+    s = gh.stream_handle()
+    f = syn.bf16_bits_to_f64
+    params, keep = [], []
+    for l in range(L):
+        wkv, gamma = bf16(rng, (2 * d_kv, d_model), 0, 0.02), bf16(rng, (d_model,), 1, 0.1)
+        beta, bias = bf16(rng, (d_model,), 0, 0.05), bf16(rng, (2 * d_kv,), 0, 0.05)
+        params.append((wkv, gamma, beta, bias))
+        dev = [gh.to_dev_bf16(a) for a in (wkv, gamma, beta, bias)]
+        keep.append(dev)
+        ctx.set_layer_weights_affine(l, *dev, s)
+    # ragged: four contexts, one launch per layer
+    lengths = np.array([130, 1, 257, 64])
+    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    T = int(cu[-1])
+    max_blocks = 20
+    num_pages = 4 * max_blocks + 5
+    perm = rng.permutation(num_pages).astype(np.int32)
+    tables = np.full((4, max_blocks), -1, dtype=np.int32)
+    at = 0
+    for i, n in enumerate(lengths):
+        nb = (n + B - 1) // B
+        tables[i, :nb] = perm[at:at + nb]
+        at += nb
+    pos = np.concatenate([np.arange(n, dtype=np.int32) for n in lengths])
+    for l in range(L):
+        x = bf16(rng, (T, d_model), 0.3, 1.0)
+        pool = gh.new_pool(num_pages, B, n_kv, hd)
+        ctx.set_kv_pool(l, pool, num_pages)
+        ctx.restore_kv_ragged(l, gh.to_dev_bf16(x), gh.to_dev_i32(pos), T, gh.to_dev_i32(cu), 4,
+                              gh.to_dev_i32(tables), max_blocks, s)
+        assert ctx.poll_device_error(s) == 0
+        wkv, gamma, beta, bias = params[l]
+        ora = np.full((num_pages, 2, B, n_kv, hd), np.nan)
+        oracle.restore_kv_ragged(ora, f(x), f(gamma), f(wkv), pos, cu, tables, beta=f(beta), bias=f(bias),
+                                 **gh.oracle_kw(desc))
+        gh.compare_pool(gh.pool_bits(pool), ora)
+    # streamed: one context from the chunk store, positions offset into the first page
+    T2, off = 300, 5
+    xs = [bf16(rng, (T2, d_model), 0.3, 1.0) for _ in range(L)]
+    store = hc.Store(L, d_model, CT, L * ((T2 + CT - 1) // CT) + 1)
+    for a, b in ((0, 200), (200, 300)):
+        for l in range(L):
+            store.append(4, l, np.ascontiguousarray(xs[l][a:b]), b - a)
+    n_blocks = (off + T2 + B - 1) // B
+    bt = rng.permutation(n_blocks + 3)[:n_blocks].astype(np.int32)
+    pools = []
+    for l in range(L):
+        pools.append(gh.new_pool(n_blocks + 3, B, n_kv, hd))
+        ctx.set_kv_pool(l, pools[l], n_blocks + 3)
+    copy_stream = torch.cuda.Stream()
+    ctx.restore_context(store, 4, 0, T2, off, gh.to_dev_i32(bt), n_blocks, s, copy_stream.cuda_stream)
+    assert ctx.poll_device_error(s) == 0
+    torch.cuda.synchronize()
+    pos2 = (off + np.arange(T2)).astype(np.int32)
+    for l in range(L):
+        wkv, gamma, beta, bias = params[l]
+        ora = np.full((n_blocks + 3, 2, B, n_kv, hd), np.nan)
+        oracle.restore_kv(ora, f(xs[l]), f(gamma), f(wkv), pos2, bt, beta=f(beta), bias=f(bias),
+                          **gh.oracle_kw(desc))
+        gh.compare_pool(gh.pool_bits(pools[l]), ora)
+    ctx.destroy()
+    store.destroy()
