@@ -173,7 +173,10 @@ hc_status hc_poll_device_error(hc_ctx* ctx, void* stream, int32_t* out_flags);
  * states of (context, layer) are a list of chunks, the last one possibly part filled.
  * Chunks are taken from the arena in the order the data arrives, i.e. in generation
  * order (layer-before-token, Section 3.2 "C2"); restoration reads them one layer at a
- * time through the index. */
+ * time through the index.  The index is guarded by a lock, so appends (also through a saver),
+ * drops, queries and restores of DIFFERENT contexts may run on different host threads; one
+ * context must not be appended to, dropped or restored concurrently, and its chunks must stay
+ * in the store until the copies a restore has queued are complete. */
 hc_status hc_store_create(int32_t n_layers, int32_t d_model, int32_t chunk_tokens,
                           int64_t capacity_chunks, hc_store** out);
 /* Same, choosing the arena's memory: pinned != 0 -> hipHostMalloc (what asynchronous,

@@ -200,9 +200,9 @@ struct hc_store {
   int64_t next_fresh = 0;                     // chunks [next_fresh, capacity) were never used
   std::vector<int64_t> free_list;             // returned chunks, reused first
   std::unordered_map<int64_t, hc_seq_state> seqs;
-  // guards the index (seqs, free_list, next_fresh) when the saver's daemon threads append
-  // concurrently; row payloads are copied outside of it
-  std::mutex index_mutex;
+  // guards the index (seqs, free_list, next_fresh): appends, drops and the readers that copy
+  // chunk lists out of it may run on different threads; row payloads are copied outside of it
+  mutable std::mutex index_mutex;
 };
 
 namespace hc {

@@ -145,6 +145,7 @@ hc_status hc_store_append(hc_store* st, int64_t seq_id, int32_t layer, const voi
 
 int64_t hc_store_tokens(const hc_store* st, int64_t seq_id, int32_t layer) {
   if (!st || layer < 0 || layer >= st->n_layers) return 0;
+  std::lock_guard<std::mutex> lock(st->index_mutex);
   auto it = st->seqs.find(seq_id);
   return it == st->seqs.end() ? 0 : it->second.tokens[layer];
 }
@@ -154,6 +155,7 @@ hc_status hc_store_chunk(const hc_store* st, int64_t seq_id, int32_t layer, int3
   clear_error();
   if (!st || !h_ptr || !rows) return fail(HC_EINVAL, "null argument");
   if (layer < 0 || layer >= st->n_layers) return fail(HC_ERANGE, "layer out of range");
+  std::lock_guard<std::mutex> lock(st->index_mutex);
   auto it = st->seqs.find(seq_id);
   if (it == st->seqs.end()) return fail(HC_ERANGE, "unknown context");
   const hc_seq_state& s = it->second;
@@ -192,17 +194,25 @@ static hc_status restore_context_impl(hc_ctx* ctx, const hc_store* hs, const hc_
   if (n_tok == 0) return HC_OK;
   if (!d_block_table) return fail(HC_EINVAL, "block table is null");
   if (compute_stream == copy_stream) return fail(HC_EINVAL, "compute and copy streams must differ");
+  // snapshot of the context's chunk lists, taken under each store's lock: appends for other
+  // contexts may run on other threads while this call enqueues its copies
+  hc_seq_state hcopy, kcopy;
   const hc_seq_state* hseq = nullptr;
   const hc_seq_state* kseq = nullptr;
   if (l_h > 0) {
+    std::lock_guard<std::mutex> lock(hs->index_mutex);
     auto it = hs->seqs.find(seq_id);
     if (it == hs->seqs.end()) return fail(HC_ERANGE, "unknown context");
-    hseq = &it->second;
+    hcopy.tokens.assign(it->second.tokens.begin(), it->second.tokens.begin() + l_h);
+    hcopy.chunks.assign(it->second.chunks.begin(), it->second.chunks.begin() + l_h);
+    hseq = &hcopy;
   }
   if (l_h < L) {
+    std::lock_guard<std::mutex> lock(ks->index_mutex);
     auto it = ks->seqs.find(seq_id);
     if (it == ks->seqs.end()) return fail(HC_ERANGE, "unknown context in the KV store");
-    kseq = &it->second;
+    kcopy = it->second;
+    kseq = &kcopy;
   }
   for (int l = 0; l < L; ++l) {
     const int64_t have = l < l_h ? hseq->tokens[l] : kseq->tokens[l - l_h];

@@ -188,3 +188,38 @@ def test_header_is_plain_c_and_links(hc, tmp_path):
     res = subprocess.run([exe], capture_output=True, text=True, timeout=60)
     assert res.returncode == 0, (res.returncode, res.stdout, res.stderr)
     assert "hcache-mi355x" in res.stdout
+
+
+def test_store_index_is_safe_across_threads(hc):
+    """Appends, queries and drops of different contexts from several host threads at once."""
+    import threading
+    L, d, CT, per_ctx = 2, 64, 4, 40
+    n_threads, rounds = 6, 30
+    st = hc.Store(L, d, CT, capacity_chunks=n_threads * L * (per_ctx // CT) + 8, pinned=False)
+    errors = []
+
+    def worker(tid):
+        try:
+            rng = np.random.default_rng(tid)
+            for r in range(rounds):
+                sid = tid * 1000 + r
+                rows = rng.integers(0, 65536, size=(per_ctx, d), dtype=np.uint16)
+                for a in range(0, per_ctx, 10):
+                    for l in range(L):
+                        st.append(sid, l, np.ascontiguousarray(rows[a:a + 10]), 10)
+                    st.tokens((tid + 1) % n_threads * 1000 + r, 0)      # someone else's context
+                for l in range(L):
+                    assert st.tokens(sid, l) == per_ctx
+                    got = np.concatenate([read_chunk(st, sid, l, c, d) for c in range(per_ctx // CT)])
+                    assert np.array_equal(got, rows)
+                st.drop(sid)
+        except Exception as e:                               # noqa: BLE001 - reported below
+            errors.append((tid, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(n_threads)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    st.destroy()
