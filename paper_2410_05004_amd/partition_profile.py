@@ -93,6 +93,22 @@ def main():
     kv_rows = torch.zeros((T, 2 * d_kv), dtype=torch.bfloat16, device="cuda")
     ctx.gather_kv(0, kv_rows, pos, T, d_bt, n_blocks, s)
     k_rows = kv_rows.view(torch.int16).cpu().numpy()
+
+    # the row <-> page copy kernels against the HBM rate (bytes read + bytes written)
+    def kernel_us(fn, reps=50):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+    kv_bytes = 2.0 * T * 2 * d_kv * 2
+    us_scatter = kernel_us(lambda: ctx.scatter_kv(0, kv_rows, pos, T, d_bt, n_blocks, s))
+    us_gather = kernel_us(lambda: ctx.gather_kv(0, kv_rows, pos, T, d_bt, n_blocks, s))
     n_chunks = -(-T // CT)
     sweep = sorted({L, L - 1, L - 2, L - 4, L * 3 // 4, L // 2, 0})
     out_sweep = []
@@ -120,7 +136,11 @@ def main():
 
     out = {"workload": w.name, "tokens": T, "layers": L,
            "io_h_ms": round(io_h, 4), "io_kv_ms": round(io_kv, 4), "c_h_ms": round(c_h, 4),
-           "c_token_ms_modelled": round(c_token, 4), "kv_complement_sweep": out_sweep}
+           "c_token_ms_modelled": round(c_token, 4), "kv_complement_sweep": out_sweep,
+           "kv_rows_kernel": {"bytes_moved_per_call": kv_bytes,
+                              "scatter_us": round(us_scatter, 2), "gather_us": round(us_gather, 2),
+                              "scatter_GBps": round(kv_bytes / us_scatter / 1e3, 1),
+                              "gather_GBps": round(kv_bytes / us_gather / 1e3, 1), "hbm_peak_GBps": 8000.0}}
     try:
         l_h, l_o, comp = hc.partition_layers(L, io_h, io_kv, c_h, c_token)
         out["partition"] = {"l_h": l_h, "l_o": l_o,
