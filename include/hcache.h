@@ -219,6 +219,17 @@ hc_status hc_restore_context(hc_ctx* ctx, const hc_store* store, int64_t seq_id,
                              const int32_t* d_block_table, int32_t n_blocks,
                              void* compute_stream, void* copy_stream);
 
+/* The same for SEVERAL stored contexts at once (the restoration phase of a batch of requests,
+ * Section 5 "Request scheduling"): tokens [0, h_n_tok[i]) of context h_seq_ids[i], i < n_seq,
+ * at positions 0 .. h_n_tok[i] - 1.  Per layer the chunks of all contexts are copied into one
+ * staging buffer, context after context, and ONE ragged launch projects them (as
+ * hc_restore_kv_ragged; d_block_tables is int32 [n_seq][max_blocks], rows padded with -1).
+ * The two host arrays are read during the call only.  Always uses the copy engines. */
+hc_status hc_restore_contexts(hc_ctx* ctx, const hc_store* store, int32_t n_seq,
+                              const int64_t* h_seq_ids, const int32_t* h_n_tok,
+                              const int32_t* d_block_tables, int32_t max_blocks,
+                              void* compute_stream, void* copy_stream);
+
 /* ---- KV-offload complement (Section 4.1.2; Figure "Two ways to combine ... with KV
  * offload", layer-wise partition) ---------------------------------------------------------
  * Layers that the partition assigns to KV offload keep their KV cache on the host as token

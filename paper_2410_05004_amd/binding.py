@@ -71,6 +71,7 @@ def _load():
         "hc_restore_context": (i32, [vp, vp, i64, i32, i32, i32, vp, i32, vp, vp]),
         "hc_gather_kv": (i32, [vp, i32, vp, vp, i32, vp, i32, vp]),
         "hc_scatter_kv": (i32, [vp, i32, vp, vp, i32, vp, i32, vp]),
+        "hc_restore_contexts": (i32, [vp, vp, i32, vp, vp, vp, i32, vp, vp]),
         "hc_restore_context_mixed": (i32, [vp, vp, vp, i32, i64, i32, i32, i32, vp, i32, vp, vp]),
         "hc_set_loader": (i32, [vp, i32]),
         "hc_partition_layers": (i32, [i32, C.c_double, C.c_double, C.c_double, C.c_double,
@@ -99,7 +100,7 @@ EXPORTED = ("hc_last_error hc_version hc_validate_desc hc_create hc_destroy hc_s
             "hc_saver_create hc_saver_destroy hc_saver_save_layer hc_saver_save_layer_host "
             "hc_saver_flush hc_partition_layers hc_gather_kv hc_scatter_kv "
             "hc_restore_context_mixed hc_set_layer_weights_affine hc_saver_save_layer_deferred "
-            "hc_saver_fence hc_restore_kv_layers").split()
+            "hc_saver_fence hc_restore_kv_layers hc_restore_contexts").split()
 
 
 def _check(status):
@@ -192,6 +193,15 @@ class Context:
                         compute_stream, copy_stream):
         _check(lib.hc_restore_context(self._h, store._h, seq_id, tok_begin, n_tok, pos_offset,
                                       _ptr(d_block_table), n_blocks, compute_stream, copy_stream))
+
+    def restore_contexts(self, store, seq_ids, n_tok, d_block_tables, max_blocks, compute_stream,
+                         copy_stream):
+        import numpy as np
+        ids = np.ascontiguousarray(seq_ids, dtype=np.int64)
+        nt = np.ascontiguousarray(n_tok, dtype=np.int32)
+        assert ids.shape == nt.shape
+        _check(lib.hc_restore_contexts(self._h, store._h, len(ids), _ptr(ids), _ptr(nt),
+                                       _ptr(d_block_tables), max_blocks, compute_stream, copy_stream))
 
     def restore_context_mixed(self, hidden_store, kv_store, l_h, seq_id, tok_begin, n_tok,
                               pos_offset, d_block_table, n_blocks, compute_stream, copy_stream):

@@ -246,6 +246,9 @@ hc_status hc_destroy(hc_ctx* ctx) {
   for (int i = 0; i < 2; ++i) {
     if (ctx->seg_tab[i]) (void)hipHostFree(ctx->seg_tab[i]);
     if (ctx->seg_done[i]) (void)hipEventDestroy(ctx->seg_done[i]);
+    if (ctx->cu_host[i]) (void)hipHostFree(ctx->cu_host[i]);
+    if (ctx->cu_dev[i]) (void)hipFree(ctx->cu_dev[i]);
+    if (ctx->cu_done[i]) (void)hipEventDestroy(ctx->cu_done[i]);
   }
   for (hipEvent_t e : ctx->ev_pool) (void)hipEventDestroy(e);
   delete ctx;

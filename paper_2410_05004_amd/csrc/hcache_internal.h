@@ -180,6 +180,13 @@ struct hc_ctx {
   size_t seg_cap[2] = {0, 0};
   hipEvent_t seg_done[2] = {nullptr, nullptr};
   int seg_next = 0;
+  // row offsets (cu_seqlens) of hc_restore_contexts: two pinned tables with device copies, used
+  // alternately, each guarded by an event recorded after the last kernel that reads it
+  int32_t* cu_host[2] = {nullptr, nullptr};
+  int32_t* cu_dev[2] = {nullptr, nullptr};
+  int cu_cap[2] = {0, 0};
+  hipEvent_t cu_done[2] = {nullptr, nullptr};
+  int cu_next = 0;
   // per-launch timing
   bool timing = false;
   std::vector<hipEvent_t> ev_pool;        // created on demand, reused

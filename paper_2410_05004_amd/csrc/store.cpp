@@ -1,6 +1,8 @@
 // Host store of saved hidden states in fixed-size token chunks (paper Section 4.2.1),
 // and the pipelined whole-context restore that reads it (Section 3.1 pipeline, Section 5
 // "Pipelined state transmission").
+#include <climits>
+#include <cstdint>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -179,6 +181,80 @@ hc_status hc_store_drop(hc_store* st, int64_t seq_id) {
   return HC_OK;
 }
 
+// ---- pieces shared by the pipelined restores ---------------------------------------------
+struct CopyRun { const unsigned char* src; unsigned char* dst; size_t row_bytes; size_t pitch; int rows; };
+
+// Two staging buffers of at least need_bytes each, and the events of the two-way handshake.
+static hc_status ensure_staging(hc_ctx* ctx, size_t need_bytes, hipStream_t cs) {
+  if (ctx->stage_bytes < need_bytes) {
+    for (int b = 0; b < 2; ++b) {
+      if (ctx->stage[b]) { HC_HIP(hipFree(ctx->stage[b])); ctx->stage[b] = nullptr; }
+    }
+    ctx->stage_bytes = 0;
+    for (int b = 0; b < 2; ++b) {
+      hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->stage[b]), need_bytes);
+      if (e != hipSuccess) {
+        (void)hipGetLastError();
+        ctx->stage[b] = nullptr;
+        return fail(HC_ENOMEM, "device allocation of a staging buffer failed");
+      }
+    }
+    ctx->stage_bytes = need_bytes;
+  }
+  for (int b = 0; b < 2; ++b) {
+    if (!ctx->h2d_done[b]) HC_HIP(hipEventCreateWithFlags(&ctx->h2d_done[b], hipEventDisableTiming));
+    if (!ctx->buf_free[b]) {
+      HC_HIP(hipEventCreateWithFlags(&ctx->buf_free[b], hipEventDisableTiming));
+      HC_HIP(hipEventRecord(ctx->buf_free[b], cs));   // nothing uses the buffer yet
+    }
+  }
+  return HC_OK;
+}
+
+// Copy-engine runs that bring tokens [tok_begin, tok_begin + n_tok) of one (context, layer) to
+// `dst` (row 0 of the range): partial first / last chunks on their own, full chunks grouped
+// while their arena slots stay equally spaced (one strided copy per group).  Appends to `runs`.
+static void build_runs(const hc_store* st, const std::vector<int64_t>& chunks, int tok_begin,
+                       int n_tok, unsigned char* dst, std::vector<CopyRun>& runs) {
+  const int CT = st->chunk_tokens;
+  const int c_first = tok_begin / CT, c_last = (tok_begin + n_tok - 1) / CT;
+  auto dst_at = [&](int c, int lo) { return dst + (size_t)(c * CT + lo - tok_begin) * st->row_bytes; };
+  auto full = [&](int cc) { return cc < c_last || tok_begin + n_tok - cc * CT == CT; };
+  int c = c_first;
+  while (c <= c_last) {
+    const int lo = c == c_first ? tok_begin - c * CT : 0;
+    const int hi = c == c_last ? tok_begin + n_tok - c * CT : CT;
+    const unsigned char* src = st->arena + (size_t)chunks[c] * st->chunk_bytes + (size_t)lo * st->row_bytes;
+    if (lo != 0 || hi != CT) {
+      runs.push_back({src, dst_at(c, lo), (size_t)(hi - lo) * st->row_bytes, 0, 1});
+      ++c;
+      continue;
+    }
+    int c_end = c;
+    int64_t stride = 0;
+    if (c + 1 <= c_last && full(c + 1)) {
+      stride = chunks[c + 1] - chunks[c];
+      if (stride > 0) {
+        c_end = c + 1;
+        while (c_end + 1 <= c_last && full(c_end + 1) && chunks[c_end + 1] - chunks[c_end] == stride) ++c_end;
+      }
+    }
+    runs.push_back({src, dst_at(c, 0), st->chunk_bytes, (size_t)stride * st->chunk_bytes, c_end - c + 1});
+    c = c_end + 1;
+  }
+}
+
+static hc_status enqueue_runs(const std::vector<CopyRun>& runs, hipStream_t xs) {
+  for (const CopyRun& r : runs) {
+    if (r.rows == 1 || r.pitch == r.row_bytes)
+      HC_HIP(hipMemcpyAsync(r.dst, r.src, r.row_bytes * r.rows, hipMemcpyHostToDevice, xs));
+    else
+      HC_HIP(hipMemcpy2DAsync(r.dst, r.row_bytes, r.src, r.pitch, r.row_bytes, r.rows,
+                              hipMemcpyHostToDevice, xs));
+  }
+  return HC_OK;
+}
+
 // Shared body of the whole-context restores.  Layers [0, l_h) come from the hidden-state
 // store `hs` through the fused kernel; layers [l_h, n_layers) come from the KV-row store `ks`
 // (layer index l - l_h there) through the row-to-page copy.  Both kinds go through the same
@@ -230,41 +306,20 @@ static hc_status restore_context_impl(hc_ctx* ctx, const hc_store* hs, const hc_
   size_t need_bytes = 0;
   if (l_h > 0) need_bytes = (size_t)n_tok * hs->row_bytes;
   if (l_h < L && (size_t)n_tok * ks->row_bytes > need_bytes) need_bytes = (size_t)n_tok * ks->row_bytes;
-  if (ctx->stage_bytes < need_bytes) {
-    for (int b = 0; b < 2; ++b) {
-      if (ctx->stage[b]) { HC_HIP(hipFree(ctx->stage[b])); ctx->stage[b] = nullptr; }
-    }
-    ctx->stage_bytes = 0;
-    for (int b = 0; b < 2; ++b) {
-      hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->stage[b]), need_bytes);
-      if (e != hipSuccess) {
-        (void)hipGetLastError();
-        ctx->stage[b] = nullptr;
-        return fail(HC_ENOMEM, "device allocation of a staging buffer failed");
-      }
-    }
-    ctx->stage_bytes = need_bytes;
-  }
-  for (int b = 0; b < 2; ++b) {
-    if (!ctx->h2d_done[b]) HC_HIP(hipEventCreateWithFlags(&ctx->h2d_done[b], hipEventDisableTiming));
-    if (!ctx->buf_free[b]) {
-      HC_HIP(hipEventCreateWithFlags(&ctx->buf_free[b], hipEventDisableTiming));
-      HC_HIP(hipEventRecord(ctx->buf_free[b], cs));   // nothing uses the buffer yet
-    }
+  {
+    hc_status r = ensure_staging(ctx, need_bytes, cs);
+    if (r != HC_OK) return r;
   }
 
   // Segments: one per run of equally spaced chunks of a layer.  Chunks that arrive in
   // generation order are spaced n_layers slots apart (or adjacent after a long prefill), so a
   // whole layer is usually a single run: one strided copy.
-  struct Run { const unsigned char* src; unsigned char* dst; size_t row_bytes; size_t pitch; int rows; };
-  std::vector<Run> runs;
+  std::vector<CopyRun> runs;
   std::vector<CopySegment> segs;                        // host scratch
   auto build = [&](const hc_store* st, const hc_seq_state& s, int l, int b) {
     const int CT = st->chunk_tokens;
     const int c_first = tok_begin / CT, c_last = (tok_begin + n_tok - 1) / CT;
-    auto stage_at = [&](int c, int lo) {
-      return reinterpret_cast<unsigned char*>(ctx->stage[b]) + (size_t)(c * CT + lo - tok_begin) * st->row_bytes;
-    };
+    unsigned char* stage = reinterpret_cast<unsigned char*>(ctx->stage[b]);
     runs.clear();
     segs.clear();
     for (int c = c_first; c <= c_last; ++c) {           // one segment per chunk (gather kernel)
@@ -272,36 +327,11 @@ static hc_status restore_context_impl(hc_ctx* ctx, const hc_store* hs, const hc_
       const int hi = c == c_last ? tok_begin + n_tok - c * CT : CT;
       CopySegment g;
       g.src = st->arena + (size_t)s.chunks[l][c] * st->chunk_bytes + (size_t)lo * st->row_bytes;
-      g.dst = stage_at(c, lo);
+      g.dst = stage + (size_t)(c * CT + lo - tok_begin) * st->row_bytes;
       g.bytes = (size_t)(hi - lo) * st->row_bytes;
       segs.push_back(g);
     }
-    // runs for the copy engines: partial first / last chunks on their own, full chunks grouped
-    // while their arena slots stay equally spaced
-    int c = c_first;
-    while (c <= c_last) {
-      const int lo = c == c_first ? tok_begin - c * CT : 0;
-      const int hi = c == c_last ? tok_begin + n_tok - c * CT : CT;
-      const unsigned char* src = st->arena + (size_t)s.chunks[l][c] * st->chunk_bytes + (size_t)lo * st->row_bytes;
-      if (lo != 0 || hi != CT) {
-        runs.push_back({src, stage_at(c, lo), (size_t)(hi - lo) * st->row_bytes, 0, 1});
-        ++c;
-        continue;
-      }
-      int c_end = c;
-      int64_t stride = 0;
-      auto full = [&](int cc) { return cc < c_last || tok_begin + n_tok - cc * CT == CT; };
-      if (c + 1 <= c_last && full(c + 1)) {
-        stride = s.chunks[l][c + 1] - s.chunks[l][c];
-        if (stride > 0) {
-          c_end = c + 1;
-          while (c_end + 1 <= c_last && full(c_end + 1) &&
-                 s.chunks[l][c_end + 1] - s.chunks[l][c_end] == stride) ++c_end;
-        }
-      }
-      runs.push_back({src, stage_at(c, 0), st->chunk_bytes, (size_t)stride * st->chunk_bytes, c_end - c + 1});
-      c = c_end + 1;
-    }
+    build_runs(st, s.chunks[l], tok_begin, n_tok, stage, runs);
   };
 
   // The gather kernel needs device-readable arenas and reads its segment table from pinned
@@ -345,13 +375,8 @@ static hc_status restore_context_impl(hc_ctx* ctx, const hc_store* hs, const hc_
       HC_HIP(launch_gather(tab + tab_used, (int)segs.size(), xs));
       tab_used += segs.size();
     } else {
-      for (const Run& r : runs) {
-        if (r.rows == 1 || r.pitch == r.row_bytes)
-          HC_HIP(hipMemcpyAsync(r.dst, r.src, r.row_bytes * r.rows, hipMemcpyHostToDevice, xs));
-        else
-          HC_HIP(hipMemcpy2DAsync(r.dst, r.row_bytes, r.src, r.pitch, r.row_bytes, r.rows,
-                                  hipMemcpyHostToDevice, xs));
-      }
+      hc_status r = enqueue_runs(runs, xs);
+      if (r != HC_OK) return r;
     }
     HC_HIP(hipEventRecord(ctx->h2d_done[b], xs));
     HC_HIP(hipStreamWaitEvent(cs, ctx->h2d_done[b], 0));
@@ -376,6 +401,96 @@ hc_status hc_restore_context(hc_ctx* ctx, const hc_store* st, int64_t seq_id, in
     return fail(HC_EINVAL, "store and context disagree on n_layers / d_model");
   return restore_context_impl(ctx, st, nullptr, ctx->desc.n_layers, seq_id, tok_begin, n_tok,
                               pos_offset, d_block_table, n_blocks, compute_stream, copy_stream);
+}
+
+hc_status hc_restore_contexts(hc_ctx* ctx, const hc_store* st, int32_t n_seq,
+                              const int64_t* h_seq_ids, const int32_t* h_n_tok,
+                              const int32_t* d_block_tables, int32_t max_blocks,
+                              void* compute_stream, void* copy_stream) {
+  clear_error();
+  if (!ctx || !st) return fail(HC_EINVAL, "null ctx or store");
+  if (st->n_layers != ctx->desc.n_layers || st->d_model != ctx->desc.d_model)
+    return fail(HC_EINVAL, "store and context disagree on n_layers / d_model");
+  if (n_seq < 0 || max_blocks < 0) return fail(HC_EINVAL, "negative size");
+  if (n_seq == 0) return HC_OK;
+  if (!h_seq_ids || !h_n_tok || !d_block_tables) return fail(HC_EINVAL, "null pointer");
+  if (compute_stream == copy_stream) return fail(HC_EINVAL, "compute and copy streams must differ");
+  const int L = ctx->desc.n_layers;
+  // snapshot of every context's chunk lists under the store's lock; row offsets
+  std::vector<hc_seq_state> snap(n_seq);
+  std::vector<int32_t> cu(n_seq + 1, 0);
+  {
+    std::lock_guard<std::mutex> lock(st->index_mutex);
+    for (int i = 0; i < n_seq; ++i) {
+      if (h_n_tok[i] < 0) return fail(HC_EINVAL, "negative token count");
+      if (h_n_tok[i] > ctx->desc.max_position) return fail(HC_ERANGE, "positions exceed max_position");
+      if ((int64_t)cu[i] + h_n_tok[i] > INT32_MAX) return fail(HC_ERANGE, "more than 2^31 rows");
+      cu[i + 1] = cu[i] + h_n_tok[i];
+      if (h_n_tok[i] == 0) continue;
+      auto it = st->seqs.find(h_seq_ids[i]);
+      if (it == st->seqs.end()) return fail(HC_ERANGE, "unknown context");
+      for (int l = 0; l < L; ++l)
+        if (it->second.tokens[l] < h_n_tok[i])
+          return fail(HC_ERANGE, "token range exceeds what the store holds for some layer");
+      snap[i] = it->second;
+    }
+  }
+  const int32_t total = cu[n_seq];
+  if (total == 0) return HC_OK;
+  for (int l = 0; l < L; ++l)
+    if (!ctx->layers[l].wpack || !ctx->layers[l].pool)
+      return fail(HC_ESTATE, "weights or KV pool missing for some layer");
+  hipStream_t cs = static_cast<hipStream_t>(compute_stream);
+  hipStream_t xs = static_cast<hipStream_t>(copy_stream);
+  hc_status r = ensure_staging(ctx, (size_t)total * st->row_bytes, cs);
+  if (r != HC_OK) return r;
+
+  // row offsets on the device: one of two tables, reused only after its last reader is done
+  const int tab = ctx->cu_next;
+  ctx->cu_next ^= 1;
+  if (!ctx->cu_done[tab]) HC_HIP(hipEventCreateWithFlags(&ctx->cu_done[tab], hipEventDisableTiming));
+  else HC_HIP(hipEventSynchronize(ctx->cu_done[tab]));
+  if (ctx->cu_cap[tab] < n_seq + 1) {
+    if (ctx->cu_host[tab]) { HC_HIP(hipHostFree(ctx->cu_host[tab])); ctx->cu_host[tab] = nullptr; }
+    if (ctx->cu_dev[tab]) { HC_HIP(hipFree(ctx->cu_dev[tab])); ctx->cu_dev[tab] = nullptr; }
+    ctx->cu_cap[tab] = 0;
+    void* p = nullptr;
+    if (hipHostMalloc(&p, (size_t)(n_seq + 1) * sizeof(int32_t), hipHostMallocDefault) != hipSuccess) {
+      (void)hipGetLastError();
+      return fail(HC_ENOMEM, "pinned allocation of the row-offset table failed");
+    }
+    ctx->cu_host[tab] = static_cast<int32_t*>(p);
+    if (hipMalloc(reinterpret_cast<void**>(&ctx->cu_dev[tab]), (size_t)(n_seq + 1) * sizeof(int32_t)) != hipSuccess) {
+      (void)hipGetLastError();
+      return fail(HC_ENOMEM, "device allocation of the row-offset table failed");
+    }
+    ctx->cu_cap[tab] = n_seq + 1;
+  }
+  memcpy(ctx->cu_host[tab], cu.data(), (size_t)(n_seq + 1) * sizeof(int32_t));
+  HC_HIP(hipMemcpyAsync(ctx->cu_dev[tab], ctx->cu_host[tab], (size_t)(n_seq + 1) * sizeof(int32_t),
+                        hipMemcpyHostToDevice, cs));
+
+  std::vector<CopyRun> runs;
+  for (int l = 0; l < L; ++l) {
+    const int b = l & 1;
+    unsigned char* stage = reinterpret_cast<unsigned char*>(ctx->stage[b]);
+    runs.clear();
+    for (int i = 0; i < n_seq; ++i)
+      if (h_n_tok[i] > 0)
+        build_runs(st, snap[i].chunks[l], 0, h_n_tok[i], stage + (size_t)cu[i] * st->row_bytes, runs);
+    HC_HIP(hipStreamWaitEvent(xs, ctx->buf_free[b], 0));
+    r = enqueue_runs(runs, xs);
+    if (r != HC_OK) return r;
+    HC_HIP(hipEventRecord(ctx->h2d_done[b], xs));
+    HC_HIP(hipStreamWaitEvent(cs, ctx->h2d_done[b], 0));
+    // positions are implied: row t of context i sits at position t - cu[i]
+    r = restore_layer(ctx, l, ctx->stage[b], nullptr, 0, total, ctx->cu_dev[tab], n_seq, d_block_tables,
+                      max_blocks, cs);
+    if (r != HC_OK) return r;
+    HC_HIP(hipEventRecord(ctx->buf_free[b], cs));
+  }
+  HC_HIP(hipEventRecord(ctx->cu_done[tab], cs));
+  return HC_OK;
 }
 
 hc_status hc_restore_context_mixed(hc_ctx* ctx, const hc_store* hidden_store,

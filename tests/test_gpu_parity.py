@@ -268,3 +268,85 @@ def test_restore_context_from_store(hc, torch, pinned, loader):
     assert e.value.status == hc.HC_EINVAL
     ctx.destroy()
     store.destroy()
+
+
+def test_restore_several_contexts_from_store(hc, torch):
+    """hc_restore_contexts: five stored contexts (one of them empty, one a single token) restored
+    together, one ragged launch per layer, positions implied by the row offsets; against the
+    oracle's ragged restore and against restoring each context on its own."""
+    rng = np.random.default_rng(63)
+    L, d_model, n_kv, hd, B, CT = 3, 512, 2, 128, 16, 64
+    lengths = np.array([200, 0, 1, 333, 64], dtype=np.int32)
+    stored = lengths + np.array([10, 5, 0, 0, 7])          # the store may hold more than is restored
+    ids = np.array([11, 5, 42, 7, 1000], dtype=np.int64)
+    desc = gh.make_desc(hc, n_layers=L, d_model=d_model, n_q_heads=n_kv, n_kv_heads=n_kv, head_dim=hd,
+                        block_size=B, max_position=512)
+    cases = [[gh.LayerCase(np.random.default_rng([63, i, l]), d_model, n_kv, hd, int(stored[i]), outliers=False)
+              for l in range(L)] for i in range(len(ids))]
+    store = hc.Store(L, d_model, CT, capacity_chunks=int(sum(-(-int(n) // CT) for n in stored)) * L + 4)
+    # interleaved arrival: contexts take turns, 50 tokens at a time, layer by layer
+    done = np.zeros(len(ids), dtype=int)
+    while np.any(done < stored):
+        for i in range(len(ids)):
+            n = int(min(50, stored[i] - done[i]))
+            if n > 0:
+                for l in range(L):
+                    store.append(int(ids[i]), l, np.ascontiguousarray(cases[i][l].x_bits[done[i]:done[i] + n]), n)
+                done[i] += n
+    max_blocks = 24
+    num_pages = len(ids) * max_blocks + 3
+    perm = rng.permutation(num_pages).astype(np.int32)
+    tables = np.full((len(ids), max_blocks), -1, dtype=np.int32)
+    at = 0
+    for i, n in enumerate(lengths):
+        nb = (int(n) + B - 1) // B
+        tables[i, :nb] = perm[at:at + nb]
+        at += nb
+    ctx = hc.Context(desc)
+    s = gh.stream_handle()
+    copy_stream = torch.cuda.Stream()
+    keep, pools = [], []
+    # all contexts of a layer share the layer's weights: take context 0's
+    for l in range(L):
+        d_w, d_g = gh.to_dev_bf16(cases[0][l].wkv_bits), gh.to_dev_bf16(cases[0][l].gamma_bits)
+        keep += [d_w, d_g]
+        ctx.set_layer_weights(l, d_w, d_g, s)
+        pools.append(gh.new_pool(num_pages, B, n_kv, hd))
+        ctx.set_kv_pool(l, pools[l], num_pages)
+    d_tables = gh.to_dev_i32(tables)
+    for rep in range(2):
+        ctx.restore_contexts(store, ids, lengths, d_tables, max_blocks, s, copy_stream.cuda_stream)
+    assert ctx.poll_device_error(s) == 0
+    torch.cuda.synchronize()
+    cu = np.concatenate([[0], np.cumsum(lengths)])
+    pos = np.concatenate([np.arange(n) for n in lengths]).astype(np.int32)
+    for l in range(L):
+        x = np.concatenate([cases[i][l].x[:lengths[i]] for i in range(len(ids))])
+        ora = np.full((num_pages, 2, B, n_kv, hd), np.nan)
+        oracle.restore_kv_ragged(ora, x, cases[0][l].gamma, cases[0][l].wkv, pos, cu, tables,
+                                 **gh.oracle_kw(desc))
+        gh.compare_pool(gh.pool_bits(pools[l]), ora)
+    # bit for bit what restoring each context alone writes
+    alone = [gh.new_pool(num_pages, B, n_kv, hd) for _ in range(L)]
+    for l in range(L):
+        ctx.set_kv_pool(l, alone[l], num_pages)
+    for i, n in enumerate(lengths):
+        if n:
+            ctx.restore_context(store, int(ids[i]), 0, int(n), 0, gh.to_dev_i32(tables[i]), max_blocks, s,
+                                copy_stream.cuda_stream)
+    torch.cuda.synchronize()
+    for l in range(L):
+        assert np.array_equal(gh.pool_bits(alone[l]), gh.pool_bits(pools[l]))
+    # errors
+    def status(*a):
+        with pytest.raises(hc.HCacheError) as e:
+            ctx.restore_contexts(*a)
+        return e.value.status
+    cs = copy_stream.cuda_stream
+    assert status(store, [11, 99], [10, 10], d_tables, max_blocks, s, cs) == hc.HC_ERANGE     # unknown context
+    assert status(store, [11], [500], d_tables, max_blocks, s, cs) == hc.HC_ERANGE             # more than stored
+    assert status(store, [11], [-1], d_tables, max_blocks, s, cs) == hc.HC_EINVAL
+    assert status(store, [11], [10], d_tables, max_blocks, s, s) == hc.HC_EINVAL
+    ctx.restore_contexts(store, [], [], d_tables, max_blocks, s, cs)                           # nothing to do
+    ctx.destroy()
+    store.destroy()
