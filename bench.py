@@ -225,7 +225,7 @@ def main():
     ctx.timing_begin()
     for _ in range(max(1, min(args.steps, 4096 // L))):
         step([stream])                                      # one stream: kernels back to back
-    avg_ms, launches = ctx.timing_end(stream)
+    avg_ms, min_ms, median_ms, launches = ctx.timing_end_stats(stream)
     layers_per_launch = L / launches * max(1, min(args.steps, 4096 // L))
     flop_per_launch = 4.0 * T * d * w.d_kv * layers_per_launch   # 2 flop per multiply-add, K and V
     achieved = flop_per_launch / (avg_ms * 1e-3) / 1e12
@@ -235,7 +235,8 @@ def main():
                 "traffic": None if args.zero_inputs or w.name not in TRAFFIC_BYTES_PER_LAUNCH
                 else (TRAFFIC_BYTES_PER_LAUNCH[w.name] if layers_per_launch == 1
                       else TRAFFIC_BYTES_PER_LAYER_FUSED[w.name] * layers_per_launch),
-                "avg_launch_us": round(avg_ms * 1e3, 2), "launches_timed": launches,
+                "avg_launch_us": round(avg_ms * 1e3, 2), "min_launch_us": round(min_ms * 1e3, 2),
+                "median_launch_us": round(median_ms * 1e3, 2), "launches_timed": launches,
                 "layers_per_launch": round(layers_per_launch, 2),
                 "flop_per_launch": flop_per_launch}
     assert ctx.poll_device_error(stream) == 0

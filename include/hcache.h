@@ -351,6 +351,9 @@ hc_status hc_set_loader(hc_ctx* ctx, int32_t mode);
  * hc_timing_end synchronises the stream.  *out_launches receives the launch count. */
 hc_status hc_timing_begin(hc_ctx* ctx);
 hc_status hc_timing_end(hc_ctx* ctx, void* stream, double* out_avg_ms, int32_t* out_launches);
+/* The same, also reporting the shortest and the median launch (either pointer may be NULL). */
+hc_status hc_timing_end_stats(hc_ctx* ctx, void* stream, double* out_avg_ms, double* out_min_ms,
+                              double* out_median_ms, int32_t* out_launches);
 
 #ifdef __cplusplus
 }

@@ -85,6 +85,7 @@ def _load():
         "hc_saver_flush": (i32, [vp]),
         "hc_timing_begin": (i32, [vp]),
         "hc_timing_end": (i32, [vp, vp, p(C.c_double), p(i32)]),
+        "hc_timing_end_stats": (i32, [vp, vp, p(C.c_double), p(C.c_double), p(C.c_double), p(i32)]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(L, name)
@@ -100,7 +101,7 @@ EXPORTED = ("hc_last_error hc_version hc_validate_desc hc_create hc_destroy hc_s
             "hc_saver_create hc_saver_destroy hc_saver_save_layer hc_saver_save_layer_host "
             "hc_saver_flush hc_partition_layers hc_gather_kv hc_scatter_kv "
             "hc_restore_context_mixed hc_set_layer_weights_affine hc_saver_save_layer_deferred "
-            "hc_saver_fence hc_restore_kv_layers hc_restore_contexts").split()
+            "hc_saver_fence hc_restore_kv_layers hc_restore_contexts hc_timing_end_stats").split()
 
 
 def _check(status):
@@ -223,6 +224,12 @@ class Context:
 
     def timing_begin(self):
         _check(lib.hc_timing_begin(self._h))
+
+    def timing_end_stats(self, stream=0):
+        """(average, shortest, median) launch in ms and the launch count."""
+        avg, mn, med, n = C.c_double(0), C.c_double(0), C.c_double(0), C.c_int32(0)
+        _check(lib.hc_timing_end_stats(self._h, stream, C.byref(avg), C.byref(mn), C.byref(med), C.byref(n)))
+        return avg.value, mn.value, med.value, n.value
 
     def timing_end(self, stream=0):
         avg, n = C.c_double(0), C.c_int32(0)

@@ -1,4 +1,5 @@
 // C ABI of libhcache.so: argument validation, context state, launches.
+#include <algorithm>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -450,22 +451,32 @@ hc_status hc_timing_begin(hc_ctx* ctx) {
   return HC_OK;
 }
 
-hc_status hc_timing_end(hc_ctx* ctx, void* stream, double* out_avg_ms, int32_t* out_launches) {
+hc_status hc_timing_end_stats(hc_ctx* ctx, void* stream, double* out_avg_ms, double* out_min_ms,
+                              double* out_median_ms, int32_t* out_launches) {
   clear_error();
   if (!ctx || !out_avg_ms || !out_launches) return fail(HC_EINVAL, "null argument");
   ctx->timing = false;
   HC_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
   double total = 0.0;
   const int n = ctx->ev_used / 2;
+  std::vector<float> all(n);
   for (int i = 0; i < n; ++i) {
     float ms = 0.f;
     HC_HIP(hipEventElapsedTime(&ms, ctx->ev_pool[2 * i], ctx->ev_pool[2 * i + 1]));
+    all[i] = ms;
     total += ms;
   }
+  std::sort(all.begin(), all.end());
   *out_launches = n;
   *out_avg_ms = n ? total / n : 0.0;
+  if (out_min_ms) *out_min_ms = n ? all[0] : 0.0;
+  if (out_median_ms) *out_median_ms = n ? (n % 2 ? all[n / 2] : 0.5 * (all[n / 2 - 1] + all[n / 2])) : 0.0;
   ctx->ev_used = 0;
   return HC_OK;
+}
+
+hc_status hc_timing_end(hc_ctx* ctx, void* stream, double* out_avg_ms, int32_t* out_launches) {
+  return hc_timing_end_stats(ctx, stream, out_avg_ms, nullptr, nullptr, out_launches);
 }
 
 }  // extern "C"
