@@ -324,7 +324,8 @@ hc_status hc_saver_flush(hc_saver* saver);
  *       l_h = ceil(n * io_kv / (io_kv + c_h - io_h));
  *   c_h <= io_h (transfer-bound): complement = token recomputation (HC_COMPLEMENT_RECOMPUTE),
  *       l_h = ceil(n * c_token / (c_token + io_h - c_h));
- *   l_o = n - l_h.  Pure host arithmetic; times in any common unit, all > 0.  The closed forms
+ *   l_o = n - l_h.  Pure host arithmetic (the ceiling of the double-precision quotient, as
+ * printed; no tolerance); times in any common unit, all > 0.  The closed forms
  * rest on the method's premises io_kv > io_h and c_token > c_h (hidden states are the smaller
  * transfer and the cheaper compute); inputs that break them -- e.g. a grouped-query model whose
  * KV cache is narrower than its hidden states -- return HC_EINVAL, since one of the plain

@@ -321,17 +321,22 @@ def restoration_time(l_h, n_layers, io_h, io_kv, c_h, c_token):
 
 def partition_layers(n_layers, io_h, io_kv, c_h, c_token):
     """The closed forms of Section 4.1.2: (l_h, l_o, complement), complement 'kv' or 're'.
-    Premises of the method: io_kv > io_h and c_token > c_h."""
+    Premises of the method: io_kv > io_h and c_token > c_h.  The ceiling is the exact one:
+    the given times are taken as the rational numbers they are, so no rounding of the
+    quotient can move the result across an integer."""
     import math
+    from fractions import Fraction
     assert io_kv > io_h and c_token > c_h
+    n = Fraction(int(n_layers))
+    io_h, io_kv, c_h, c_token = (Fraction(float(t)) for t in (io_h, io_kv, c_h, c_token))
     if c_h > io_h:
-        l_h = math.ceil(n_layers * io_kv / (io_kv + c_h - io_h) - 1e-9 * n_layers)
+        l_h = math.ceil(n * io_kv / (io_kv + c_h - io_h))
         comp = "kv"
     else:
-        l_h = math.ceil(n_layers * c_token / (c_token + io_h - c_h) - 1e-9 * n_layers)
+        l_h = math.ceil(n * c_token / (c_token + io_h - c_h))
         comp = "re"
-    l_h = min(max(l_h, 0), n_layers)
-    return l_h, n_layers - l_h, comp
+    l_h = min(max(l_h, 0), int(n_layers))
+    return l_h, int(n_layers) - l_h, comp
 
 
 # --------------------------------------------------------------- cost accounting

@@ -1,5 +1,6 @@
 // C ABI of libhcache.so: argument validation, context state, launches.
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -425,9 +426,8 @@ hc_status hc_partition_layers(int32_t n_layers, double io_h, double io_kv, doubl
     *complement = HC_COMPLEMENT_RECOMPUTE;
     x = n_layers * c_token / (c_token + io_h - c_h);
   }
-  // ceil with a guard against a quotient that lands a few ulps above an integer
-  int32_t lh = (int32_t)x;
-  if ((double)lh < x - 1e-9 * (double)n_layers) ++lh;
+  // the ceiling as printed, on the double-precision quotient
+  int32_t lh = (int32_t)std::ceil(x);
   if (lh > n_layers) lh = n_layers;
   if (lh < 0) lh = 0;
   *l_h = lh;

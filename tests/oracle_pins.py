@@ -590,6 +590,11 @@ def check_partition(o):
     assert o.partition_layers(48, 1.0, 2.0, 0.5, 2.4) == (40, 8, "re")   # 48*2.4/2.9 = 39.7
     # balanced platform: everything from hidden states
     assert o.partition_layers(32, 1.0, 2.0, 1.0, 9.0) == (32, 0, "re")
+    # the ceiling is exact.  90 / 10 = 9 layers; shaving 2^-30 off the denominator puts the
+    # quotient 8.4e-10 above 9, so the printed formula says 10; a quotient exactly at 9 stays 9
+    assert o.partition_layers(10, 1.0, 9.0, 2.0, 50.0) == (9, 1, "kv")
+    assert o.partition_layers(10, 1.0, 9.0, 2.0 - 2.0 ** -30, 50.0) == (10, 0, "kv")
+    assert o.partition_layers(10, 1.0, 9.0, 2.0 + 2.0 ** -30, 50.0) == (9, 1, "kv")
 
 
 # --------------------------------------------------------------- cost accounting

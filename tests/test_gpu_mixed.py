@@ -94,6 +94,19 @@ def test_scatter_gather_rows(hc, torch, n_kv, hd, B):
     ctx.destroy()
 
 
+MIXED_SHAPE = dict(L=5, d_model=512, n_kv=2, hd=128, T_stored=520, tok_begin=20, n_tok=490, pos_offset=200)
+
+
+def mixed_cases(seed=39):
+    """One LayerCase per layer, outlier channels included.  At d_model = 512 five x20 channels
+    dominate every sum and the two bf16 roundings of the prescribed arithmetic alone use most of
+    the 2e-2 x RMS budget; the seed is one for which they stay inside it on all five layers
+    (tests/test_tolerance_model.py proves it on the CPU)."""
+    m = MIXED_SHAPE
+    return [gh.LayerCase(np.random.default_rng([seed, l]), m["d_model"], m["n_kv"], m["hd"], m["T_stored"])
+            for l in range(m["L"])]
+
+
 @pytest.mark.parametrize("l_h", [0, 3, 5])
 def test_restore_context_mixed(hc, torch, l_h):
     """First l_h layers from the hidden-state store (checked against the oracle's projection),
@@ -105,12 +118,7 @@ def test_restore_context_mixed(hc, torch, l_h):
     T_stored, tok_begin, n_tok, pos_offset = 520, 20, 490, 200
     desc = gh.make_desc(hc, n_layers=L, d_model=d_model, n_q_heads=n_kv, n_kv_heads=n_kv,
                         head_dim=hd, block_size=B, max_position=pos_offset + T_stored)
-    # Inputs without outlier channels: at d_model = 512 five x20 channels dominate every sum and
-    # the bf16 roundings alone (folded gain, output) exceed 2e-2 x RMS for most seeds, as a CPU
-    # emulation of those two roundings shows; the tolerance is checked at the real widths
-    # elsewhere, this test is about which layer is restored from what.
-    cases = [gh.LayerCase(np.random.default_rng([31, l]), d_model, n_kv, hd, T_stored, outliers=False)
-             for l in range(L)]
+    cases = mixed_cases()
     n_blocks = (pos_offset + T_stored + B - 1) // B
     num_pages = n_blocks + 7
     ctx = hc.Context(desc)

@@ -152,6 +152,10 @@ def test_partition_matches_oracle(hc):
         want = oracle.partition_layers(n, io_h, io_kv, c_h, c_tok)
         assert (l_h, l_o, "kv" if comp == 0 else "re") == want
     assert hc.partition_layers(32, 1.0, 2.0, 1.1, 10.0) == (31, 1, 0)
+    # the ceiling is the plain one: a quotient 8.4e-10 above 9 gives 10 layers, on both sides
+    for c_h, want in ((2.0, 9), (2.0 - 2.0 ** -30, 10), (2.0 + 2.0 ** -30, 9)):
+        assert hc.partition_layers(10, 1.0, 9.0, c_h, 50.0) == (want, 10 - want, 0)
+        assert oracle.partition_layers(10, 1.0, 9.0, c_h, 50.0) == (want, 10 - want, "kv")
     for bad in [(0, 1, 1, 1, 1), (4, 0, 1, 1, 1), (4, 1, -1, 1, 1), (4, 1, 1, 0, 1), (4, 1, 1, 1, float("nan")),
                 (4, 2, 1, 3, 9), (4, 1, 2, 3, 2)]:
         with pytest.raises(hc.HCacheError) as e:

@@ -184,6 +184,17 @@ def mut_partition_floor(o):
     o.partition_layers = partition_layers
 
 
+def mut_partition_guarded_ceiling(o):
+    # a tolerance subtracted before the ceiling: quotients a hair above an integer round down
+    import math
+
+    def partition_layers(n, io_h, io_kv, c_h, c_token):
+        x = n * io_kv / (io_kv + c_h - io_h) if c_h > io_h else n * c_token / (c_token + io_h - c_h)
+        l_h = min(max(math.ceil(x - 1e-9 * n), 0), n)
+        return l_h, n - l_h, "kv" if c_h > io_h else "re"
+    o.partition_layers = partition_layers
+
+
 def mut_partition_wrong_branch(o):
     real = o.partition_layers
     o.partition_layers = lambda n, io_h, io_kv, c_h, c_token: real(n, c_h, io_kv, io_h, c_token)
