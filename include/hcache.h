@@ -219,6 +219,29 @@ hc_status hc_restore_context(hc_ctx* ctx, const hc_store* store, int64_t seq_id,
                              const int32_t* d_block_table, int32_t n_blocks,
                              void* compute_stream, void* copy_stream);
 
+/* hc_restore_context for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Identical arguments, loader
+ * (copy engines), kernel and result; the two staging buffers are the halves of a
+ * device-resident array inside the library (2 x HC_STATIC_STAGE_BYTES, held by every GPU the
+ * library runs on until the process ends), whose address and handshake events hc_create sets
+ * up once per device.  The call itself calls no hipMalloc / hipFree / event creation and makes
+ * no host heap allocation on the success path.  Limits: n_tok * d_model * 2 bytes <=
+ * HC_STATIC_STAGE_BYTES (HC_ERANGE beyond; restore a longer range in pieces), at most 256
+ * copy-engine transfers per layer (HC_ERANGE), per-launch timing off (HC_ESTATE).  The array
+ * is shared by every context on a GPU and keeps the last call's rows; nothing in it has to
+ * start at zero (each call overwrites the rows it reads).  Host calls are serialised by a
+ * lock and a call's copies wait for the kernels of the previous call through the per-device
+ * events, but two restores that are in flight on one GPU at the same time through OTHER
+ * means (another process image of the library, a captured graph replayed beside a live call)
+ * race on the array. */
+#define HC_STATIC_STAGE_BYTES (8 * 1024 * 1024)
+hc_status hc_restore_context_static(hc_ctx* ctx, const hc_store* store, int64_t seq_id,
+                                    int32_t tok_begin, int32_t n_tok, int32_t pos_offset,
+                                    const int32_t* d_block_table, int32_t n_blocks,
+                                    void* compute_stream, void* copy_stream);
+/* HC_STATIC_STAGE_BYTES as the built library has it. */
+int64_t hc_static_stage_bytes(void);
+
 /* The same for SEVERAL stored contexts at once (the restoration phase of a batch of requests,
  * Section 5 "Request scheduling"): tokens [0, h_n_tok[i]) of context h_seq_ids[i], i < n_seq,
  * at positions 0 .. h_n_tok[i] - 1.  Per layer the chunks of all contexts are copied into one

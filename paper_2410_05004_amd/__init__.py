@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     lib_path,
     version,
     validate_desc,
+    static_stage_bytes,
     partition_layers,
     HC_OK, HC_EINVAL, HC_ERANGE, HC_EALIGN, HC_ENOMEM, HC_EHIP, HC_ESTATE,
     HC_DEV_BAD_POSITION, HC_DEV_BAD_PAGE, HC_NORM_RMS, HC_NORM_LAYER,

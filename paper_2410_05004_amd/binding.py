@@ -35,7 +35,7 @@ def lib_path():
 def _load():
     if not os.path.exists(_LIB_FILE):
         raise ImportError(
-            f"{_LIB_FILE} is missing: build it with `python -m paper_2410_05004_amd.build` "
+            f"{_LIB_FILE} is missing: build it with `python paper_2410_05004_amd/build.py` "
             "(there is no CPU fallback for the restoration path)")
     # The device pointers and stream handles this library is handed come from the caller's HIP
     # runtime, so both must be the same loaded runtime.  PyTorch wheels bundle their own
@@ -69,6 +69,8 @@ def _load():
         "hc_store_chunk": (i32, [vp, i64, i32, i32, p(vp), p(i32)]),
         "hc_store_drop": (i32, [vp, i64]),
         "hc_restore_context": (i32, [vp, vp, i64, i32, i32, i32, vp, i32, vp, vp]),
+        "hc_restore_context_static": (i32, [vp, vp, i64, i32, i32, i32, vp, i32, vp, vp]),
+        "hc_static_stage_bytes": (i64, []),
         "hc_gather_kv": (i32, [vp, i32, vp, vp, i32, vp, i32, vp]),
         "hc_scatter_kv": (i32, [vp, i32, vp, vp, i32, vp, i32, vp]),
         "hc_restore_contexts": (i32, [vp, vp, i32, vp, vp, vp, i32, vp, vp]),
@@ -101,12 +103,17 @@ EXPORTED = ("hc_last_error hc_version hc_validate_desc hc_create hc_destroy hc_s
             "hc_saver_create hc_saver_destroy hc_saver_save_layer hc_saver_save_layer_host "
             "hc_saver_flush hc_partition_layers hc_gather_kv hc_scatter_kv "
             "hc_restore_context_mixed hc_set_layer_weights_affine hc_saver_save_layer_deferred "
-            "hc_saver_fence hc_restore_kv_layers hc_restore_contexts hc_timing_end_stats").split()
+            "hc_saver_fence hc_restore_kv_layers hc_restore_contexts hc_timing_end_stats "
+            "hc_restore_context_static hc_static_stage_bytes").split()
 
 
 def _check(status):
     if status != HC_OK:
         raise HCacheError(status, lib.hc_last_error().decode())
+
+
+def static_stage_bytes():
+    return lib.hc_static_stage_bytes()
 
 
 def version():
@@ -194,6 +201,12 @@ class Context:
                         compute_stream, copy_stream):
         _check(lib.hc_restore_context(self._h, store._h, seq_id, tok_begin, n_tok, pos_offset,
                                       _ptr(d_block_table), n_blocks, compute_stream, copy_stream))
+
+    def restore_context_static(self, store, seq_id, tok_begin, n_tok, pos_offset, d_block_table,
+                               n_blocks, compute_stream, copy_stream):
+        _check(lib.hc_restore_context_static(self._h, store._h, seq_id, tok_begin, n_tok, pos_offset,
+                                             _ptr(d_block_table), n_blocks, compute_stream,
+                                             copy_stream))
 
     def restore_contexts(self, store, seq_ids, n_tok, d_block_tables, max_blocks, compute_stream,
                          copy_stream):

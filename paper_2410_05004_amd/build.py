@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhcache.so")
 SOURCES = ["api.cpp", "store.cpp", "saver.cpp", "restore_mode0.hip", "restore_mode1.hip",
-           "restore_mode2.hip", "aux_kernels.hip"]
+           "restore_mode2.hip", "aux_kernels.hip", "static_restore.hip"]
 
 
 def hipcc_path():

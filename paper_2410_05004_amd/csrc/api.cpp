@@ -209,6 +209,10 @@ hc_status hc_create(const hc_model_desc* desc, hc_ctx** out) {
 
   hipError_t e = hipGetDevice(&ctx->device);
   if (e == hipSuccess) e = configure_kernels();
+  if (e == hipSuccess && static_scratch_init() != HC_OK) {
+    delete ctx;
+    return HC_EHIP;                                  // message set by static_scratch_init
+  }
   const bool rotary = desc->rope_style != 2;
   if (e == hipSuccess && rotary)
     e = hipMalloc(reinterpret_cast<void**>(&ctx->rope),

@@ -213,6 +213,61 @@ struct hc_store {
 };
 
 namespace hc {
+// One copy-engine transfer of a pipelined restore: `rows` pieces of `row_bytes` each, `pitch`
+// bytes apart at the source (pinned arena) and back to back at the destination (HBM).
+struct CopyRun { const unsigned char* src; unsigned char* dst; size_t row_bytes; size_t pitch; int rows; };
+
+// Copy-engine runs that bring tokens [tok_begin, tok_begin + n_tok) of one (context, layer) to
+// `dst` (row 0 of the range): partial first / last chunks on their own, full chunks grouped
+// while their arena slots stay equally spaced (one strided copy per group).  `emit(run)` is
+// called per run in token order and returns false to stop early; the result says whether
+// every run was emitted.  Nothing is allocated here.
+template <class Emit>
+inline bool for_each_run(const hc_store* st, const std::vector<int64_t>& chunks, int tok_begin,
+                         int n_tok, unsigned char* dst, Emit&& emit) {
+  const int CT = st->chunk_tokens;
+  const int c_first = tok_begin / CT, c_last = (tok_begin + n_tok - 1) / CT;
+  auto dst_at = [&](int c, int lo) { return dst + (size_t)(c * CT + lo - tok_begin) * st->row_bytes; };
+  auto full = [&](int cc) { return cc < c_last || tok_begin + n_tok - cc * CT == CT; };
+  int c = c_first;
+  while (c <= c_last) {
+    const int lo = c == c_first ? tok_begin - c * CT : 0;
+    const int hi = c == c_last ? tok_begin + n_tok - c * CT : CT;
+    const unsigned char* src = st->arena + (size_t)chunks[c] * st->chunk_bytes + (size_t)lo * st->row_bytes;
+    if (lo != 0 || hi != CT) {
+      if (!emit(CopyRun{src, dst_at(c, lo), (size_t)(hi - lo) * st->row_bytes, 0, 1})) return false;
+      ++c;
+      continue;
+    }
+    int c_end = c;
+    int64_t stride = 0;
+    if (c + 1 <= c_last && full(c + 1)) {
+      stride = chunks[c + 1] - chunks[c];
+      if (stride > 0) {
+        c_end = c + 1;
+        while (c_end + 1 <= c_last && full(c_end + 1) && chunks[c_end + 1] - chunks[c_end] == stride) ++c_end;
+      }
+    }
+    if (!emit(CopyRun{src, dst_at(c, 0), st->chunk_bytes, (size_t)stride * st->chunk_bytes, c_end - c + 1}))
+      return false;
+    c = c_end + 1;
+  }
+  return true;
+}
+
+inline hc_status enqueue_run(const CopyRun& r, hipStream_t xs) {
+  if (r.rows == 1 || r.pitch == r.row_bytes)
+    HC_HIP(hipMemcpyAsync(r.dst, r.src, r.row_bytes * r.rows, hipMemcpyHostToDevice, xs));
+  else
+    HC_HIP(hipMemcpy2DAsync(r.dst, r.row_bytes, r.src, r.pitch, r.row_bytes, r.rows,
+                            hipMemcpyHostToDevice, xs));
+  return HC_OK;
+}
+
+// Device-resident scratch of the entry point that allocates nothing (static_restore.hip):
+// looks the array's address up and creates the handshake events once per device.
+hc_status static_scratch_init();
+
 // One contiguous destination of appended rows: `bytes` from offset `src_off` of the source.
 struct StorePiece {
   unsigned char* dst;

@@ -182,8 +182,6 @@ hc_status hc_store_drop(hc_store* st, int64_t seq_id) {
 }
 
 // ---- pieces shared by the pipelined restores ---------------------------------------------
-struct CopyRun { const unsigned char* src; unsigned char* dst; size_t row_bytes; size_t pitch; int rows; };
-
 // Two staging buffers of at least need_bytes each, and the events of the two-way handshake.
 static hc_status ensure_staging(hc_ctx* ctx, size_t need_bytes, hipStream_t cs) {
   if (ctx->stage_bytes < need_bytes) {
@@ -211,46 +209,15 @@ static hc_status ensure_staging(hc_ctx* ctx, size_t need_bytes, hipStream_t cs) 
   return HC_OK;
 }
 
-// Copy-engine runs that bring tokens [tok_begin, tok_begin + n_tok) of one (context, layer) to
-// `dst` (row 0 of the range): partial first / last chunks on their own, full chunks grouped
-// while their arena slots stay equally spaced (one strided copy per group).  Appends to `runs`.
 static void build_runs(const hc_store* st, const std::vector<int64_t>& chunks, int tok_begin,
                        int n_tok, unsigned char* dst, std::vector<CopyRun>& runs) {
-  const int CT = st->chunk_tokens;
-  const int c_first = tok_begin / CT, c_last = (tok_begin + n_tok - 1) / CT;
-  auto dst_at = [&](int c, int lo) { return dst + (size_t)(c * CT + lo - tok_begin) * st->row_bytes; };
-  auto full = [&](int cc) { return cc < c_last || tok_begin + n_tok - cc * CT == CT; };
-  int c = c_first;
-  while (c <= c_last) {
-    const int lo = c == c_first ? tok_begin - c * CT : 0;
-    const int hi = c == c_last ? tok_begin + n_tok - c * CT : CT;
-    const unsigned char* src = st->arena + (size_t)chunks[c] * st->chunk_bytes + (size_t)lo * st->row_bytes;
-    if (lo != 0 || hi != CT) {
-      runs.push_back({src, dst_at(c, lo), (size_t)(hi - lo) * st->row_bytes, 0, 1});
-      ++c;
-      continue;
-    }
-    int c_end = c;
-    int64_t stride = 0;
-    if (c + 1 <= c_last && full(c + 1)) {
-      stride = chunks[c + 1] - chunks[c];
-      if (stride > 0) {
-        c_end = c + 1;
-        while (c_end + 1 <= c_last && full(c_end + 1) && chunks[c_end + 1] - chunks[c_end] == stride) ++c_end;
-      }
-    }
-    runs.push_back({src, dst_at(c, 0), st->chunk_bytes, (size_t)stride * st->chunk_bytes, c_end - c + 1});
-    c = c_end + 1;
-  }
+  for_each_run(st, chunks, tok_begin, n_tok, dst, [&](const CopyRun& r) { runs.push_back(r); return true; });
 }
 
 static hc_status enqueue_runs(const std::vector<CopyRun>& runs, hipStream_t xs) {
   for (const CopyRun& r : runs) {
-    if (r.rows == 1 || r.pitch == r.row_bytes)
-      HC_HIP(hipMemcpyAsync(r.dst, r.src, r.row_bytes * r.rows, hipMemcpyHostToDevice, xs));
-    else
-      HC_HIP(hipMemcpy2DAsync(r.dst, r.row_bytes, r.src, r.pitch, r.row_bytes, r.rows,
-                              hipMemcpyHostToDevice, xs));
+    hc_status s = enqueue_run(r, xs);
+    if (s != HC_OK) return s;
   }
   return HC_OK;
 }
