@@ -127,7 +127,8 @@ hc_status hc_set_layer_weights_affine(hc_ctx* ctx, int32_t layer, const void* d_
                                       const void* d_bias, void* stream);
 
 /* Register one layer's paged KV pool (borrowed, never freed by the library):
- *   d_pool bf16 [num_pages][2 (0=K,1=V)][block_size][n_kv_heads][head_dim]            */
+ *   d_pool bf16 [num_pages][2 (0=K,1=V)][block_size][n_kv_heads][head_dim]
+ * num_pages * 2 * block_size must stay below 2^31 (HC_ERANGE). */
 hc_status hc_set_kv_pool(hc_ctx* ctx, int32_t layer, void* d_pool, int64_t num_pages);
 
 /* Restore layer `layer` of ONE context from hidden states already in HBM
@@ -218,6 +219,12 @@ hc_status hc_restore_context(hc_ctx* ctx, const hc_store* store, int64_t seq_id,
                              int32_t tok_begin, int32_t n_tok, int32_t pos_offset,
                              const int32_t* d_block_table, int32_t n_blocks,
                              void* compute_stream, void* copy_stream);
+
+/* Test hook: fill both staging buffers of the context with a bf16 NaN pattern (0x7FFF), on
+ * `compute_stream` after everything queued there, and make the next restore's copies wait for
+ * the fill.  A restore that afterwards reads any staging row it did not copy itself produces
+ * NaNs, which the parity tests detect.  HC_ESTATE before the first hc_restore_context*. */
+hc_status hc_poison_staging(hc_ctx* ctx, void* compute_stream);
 
 /* hc_restore_context for callers that cannot allocate device memory: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Identical arguments, loader

@@ -71,6 +71,7 @@ def _load():
         "hc_restore_context": (i32, [vp, vp, i64, i32, i32, i32, vp, i32, vp, vp]),
         "hc_restore_context_static": (i32, [vp, vp, i64, i32, i32, i32, vp, i32, vp, vp]),
         "hc_static_stage_bytes": (i64, []),
+        "hc_poison_staging": (i32, [vp, vp]),
         "hc_gather_kv": (i32, [vp, i32, vp, vp, i32, vp, i32, vp]),
         "hc_scatter_kv": (i32, [vp, i32, vp, vp, i32, vp, i32, vp]),
         "hc_restore_contexts": (i32, [vp, vp, i32, vp, vp, vp, i32, vp, vp]),
@@ -104,7 +105,7 @@ EXPORTED = ("hc_last_error hc_version hc_validate_desc hc_create hc_destroy hc_s
             "hc_saver_flush hc_partition_layers hc_gather_kv hc_scatter_kv "
             "hc_restore_context_mixed hc_set_layer_weights_affine hc_saver_save_layer_deferred "
             "hc_saver_fence hc_restore_kv_layers hc_restore_contexts hc_timing_end_stats "
-            "hc_restore_context_static hc_static_stage_bytes").split()
+            "hc_restore_context_static hc_static_stage_bytes hc_poison_staging").split()
 
 
 def _check(status):
@@ -201,6 +202,9 @@ class Context:
                         compute_stream, copy_stream):
         _check(lib.hc_restore_context(self._h, store._h, seq_id, tok_begin, n_tok, pos_offset,
                                       _ptr(d_block_table), n_blocks, compute_stream, copy_stream))
+
+    def poison_staging(self, compute_stream):
+        _check(lib.hc_poison_staging(self._h, compute_stream))
 
     def restore_context_static(self, store, seq_id, tok_begin, n_tok, pos_offset, d_block_table,
                                n_blocks, compute_stream, copy_stream):

@@ -320,8 +320,9 @@ hc_status hc_set_kv_pool(hc_ctx* ctx, int32_t layer, void* d_pool, int64_t num_p
   if (s != HC_OK) return s;
   if (!d_pool) return fail(HC_EINVAL, "pool pointer is null");
   if (!aligned16(d_pool)) return fail(HC_EALIGN, "pool not 16-byte aligned");
-  if (num_pages <= 0 || num_pages > ((int64_t)1 << 31) - 1)
-    return fail(HC_ERANGE, "num_pages out of range");
+  // the kernels number a pool's token rows (2 * block_size per page) with 32-bit integers
+  if (num_pages <= 0 || num_pages * 2 * ctx->desc.block_size > ((int64_t)1 << 31) - 1)
+    return fail(HC_ERANGE, "num_pages out of range (num_pages * 2 * block_size must stay below 2^31)");
   ctx->layers[layer].pool = static_cast<uint16_t*>(d_pool);
   ctx->layers[layer].num_pages = num_pages;
   return HC_OK;

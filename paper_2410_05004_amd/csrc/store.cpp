@@ -370,6 +370,20 @@ hc_status hc_restore_context(hc_ctx* ctx, const hc_store* st, int64_t seq_id, in
                               pos_offset, d_block_table, n_blocks, compute_stream, copy_stream);
 }
 
+hc_status hc_poison_staging(hc_ctx* ctx, void* compute_stream) {
+  clear_error();
+  if (!ctx) return fail(HC_EINVAL, "null ctx");
+  if (!ctx->stage[0] || !ctx->stage[1] || !ctx->buf_free[0] || !ctx->buf_free[1])
+    return fail(HC_ESTATE, "the context has no staging buffers yet");
+  hipStream_t cs = static_cast<hipStream_t>(compute_stream);
+  for (int b = 0; b < 2; ++b) {
+    // after every kernel queued on the stream so far; the next restore's copies wait for it
+    HC_HIP(hipMemsetD16Async(reinterpret_cast<hipDeviceptr_t>(ctx->stage[b]), 0x7FFF, ctx->stage_bytes / 2, cs));
+    HC_HIP(hipEventRecord(ctx->buf_free[b], cs));
+  }
+  return HC_OK;
+}
+
 hc_status hc_restore_contexts(hc_ctx* ctx, const hc_store* st, int32_t n_seq,
                               const int64_t* h_seq_ids, const int32_t* h_n_tok,
                               const int32_t* d_block_tables, int32_t max_blocks,

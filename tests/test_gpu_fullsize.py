@@ -10,7 +10,12 @@ The oracle cannot afford every output at these sizes, so each layer is checked b
         seeded random tokens, all features;
   (iii) a whole-tensor random-projection check in fp64 for EVERY token: for a seeded
         vector r, <V_gpu[t], r> and <unrotated K_gpu[t], r> against <x_hat[t], W^T r>.
-Two layers per workload (first and last) keep the run short.
+Workloads 1 and 3 take two layers (first and last).  The streamed workloads go through the
+layer pipeline at full depth: all 32 layers of workload 2 and 8 consecutive middle layers of
+workload 4, every layer with its own seeded input, so that both staging buffers are reused
+many times while the kernel is much shorter than the copy; check (ii) runs on a few of
+those layers (first, middle ones, last), checks (i) and (iii) on every layer.  Between two
+restores both staging buffers are filled with a NaN pattern.
 """
 import numpy as np
 import pytest
@@ -18,6 +23,7 @@ import pytest
 import synthetic as syn
 import oracle.hcache_oracle as oracle
 import gpu_harness as gh
+import arith_model
 
 pytestmark = pytest.mark.gpu
 
@@ -61,8 +67,15 @@ def check_layer(w, desc, bits, x_bits, wkv_bits, gamma_bits, pos, seq_of_row, ta
     got = syn.bf16_bits_to_f64(bits[page, :, slot])           # [T, 2, H, hd] in token order
     assert np.all(np.isfinite(got))
 
-    # (ii) sampled tokens, every feature
+    # (ii) sampled tokens, every feature.  rows = None: this layer is not one of the few that
+    # are held to the tolerance against the unrounded oracle element by element (the prescribed
+    # bf16 arithmetic itself sits at 1.7e-2 - 2.2e-2 x RMS_head, tests/test_tolerance_model.py);
+    # 256 seeded rows are then compared with the CPU model of that arithmetic instead, to one
+    # bf16 step, which is the tighter check of the kernel.
     xf = syn.bf16_bits_to_f64(x_bits)                          # [T, d]
+    sampled = rows is not None
+    if not sampled:
+        rows = np.sort(rng.choice(T, size=min(256, T), replace=False))
     xs = xf[rows]
     beta = None if beta_bits is None else syn.bf16_bits_to_f64(beta_bits)
     bias = None if bias_bits is None else syn.bf16_bits_to_f64(bias_bits)
@@ -76,7 +89,14 @@ def check_layer(w, desc, bits, x_bits, wkv_bits, gamma_bits, pos, seq_of_row, ta
         rms_kv.append(np.sqrt(np.mean(ref * ref)))
         err = np.max(np.abs(g - ref), axis=(0, 2))
         worst = max(worst, float(np.max(err / rms)))
-    assert worst <= gh.TOL, f"sampled rows: max |err| = {worst:.3e} x per-head RMS"
+    if sampled:
+        assert worst <= gh.TOL, f"sampled rows: max |err| = {worst:.3e} x per-head RMS"
+    if kw["norm"] == "rms":
+        km, vm = arith_model.restore_rows(xs, gamma, wkv, pos[rows], eps=kw["eps"], theta=kw["theta"],
+                                          n_kv_heads=H, head_dim=hd, rope_style=kw["rope_style"], bias=bias)
+        model_bits = np.stack([syn.f32_to_bf16_bits(km.astype(np.float32)),
+                               syn.f32_to_bf16_bits(vm.astype(np.float32))], axis=1)
+        gh.assert_close_to_model(bits[page[rows], :, slot[rows]], model_bits)
 
     # (iii) random projection over all tokens
     r = rng.standard_normal(H * hd)
@@ -109,14 +129,12 @@ def layers_under_test(w):
     return (0, w.n_layers - 1)
 
 
-@pytest.mark.parametrize("index", [1, 2, 4])
+@pytest.mark.parametrize("index", [1])
 def test_single_context_workloads(hc, index):
-    """Workload 1 from HBM through hc_restore_kv; workloads 2 and 4 streamed from the pinned
-    chunk store through hc_restore_context (positions offset by 1000 in workload 4)."""
+    """Workload 1 from HBM through hc_restore_kv."""
     import torch
     w = syn.WORKLOADS[index]
     T, B = w.tokens, w.block_size
-    streamed = index in (2, 4)
     layers = layers_under_test(w)
     # a context holding just the layers under test (each layer's work is independent)
     desc = gh.make_desc(hc, n_layers=len(layers), d_model=w.d_model, n_q_heads=w.n_q_heads,
@@ -138,21 +156,10 @@ def test_single_context_workloads(hc, index):
         pools.append(gh.new_pool(num_pages, B, w.n_kv_heads, w.head_dim))
         ctx.set_kv_pool(i, pools[i], num_pages)
     print(f"{w.name}: inputs ready", flush=True)
-    if streamed:
-        CT = w.chunk_tokens
-        n_chunks = (T + CT - 1) // CT
-        store = hc.Store(len(layers), w.d_model, CT, len(layers) * n_chunks, pinned=True)
-        for c in range(n_chunks):
-            for i in range(len(layers)):
-                rows = data[i][2][c * CT:(c + 1) * CT]
-                store.append(0, i, rows, len(rows))
-        copy_stream = torch.cuda.Stream()
-        ctx.restore_context(store, 0, 0, T, w.pos_offset, d_bt, len(bt), s, copy_stream.cuda_stream)
-    else:
-        d_pos = gh.to_dev_i32(pos)
-        for i in range(len(layers)):
-            d_x = gh.to_dev_bf16(data[i][2])
-            ctx.restore_kv(i, d_x, d_pos, T, d_bt, len(bt), s)
+    d_pos = gh.to_dev_i32(pos)
+    for i in range(len(layers)):
+        d_x = gh.to_dev_bf16(data[i][2])
+        ctx.restore_kv(i, d_x, d_pos, T, d_bt, len(bt), s)
     assert ctx.poll_device_error(s) == 0
     torch.cuda.synchronize()
     print(f"{w.name}: restored", flush=True)
@@ -166,8 +173,75 @@ def test_single_context_workloads(hc, index):
         print(f"{w.name} layer {l}: sampled worst {res[0]:.3e} x RMS_head; projection check "
               f"K {res[1]:.3f} V {res[2]:.3f} of limit", flush=True)
     ctx.destroy()
-    if streamed:
-        store.destroy()
+
+
+@pytest.mark.parametrize("index,layers,sampled_layers", [
+    (2, tuple(range(32)), (0, 9, 16, 22, 31)),
+    (4, tuple(range(36, 44)), (36, 39, 43)),
+], ids=["llama3-8b-gqa-T8192-all-32-layers", "70b-gqa-T32768-layers-36-43"])
+def test_streamed_workloads_full_depth(hc, index, layers, sampled_layers):
+    """hc_restore_context over a deep stack at full size: the kernel of a layer (0.12 ms / 0.9 ms)
+    is far shorter than the layer's copy (1.2 ms / 9.5 ms), so the loader runs ahead as far as
+    the two staging buffers allow and every buffer is refilled many times.  Restore once, fill
+    both staging buffers with NaNs, restore again into fresh pools: the two results must be
+    bit-identical and every layer must pass checks (i) and (iii); a few layers also (ii)."""
+    import torch
+    from concurrent.futures import ThreadPoolExecutor
+    w = syn.WORKLOADS[index]
+    T, B, CT, L = w.tokens, w.block_size, w.chunk_tokens, len(layers)
+    desc = gh.make_desc(hc, n_layers=L, d_model=w.d_model, n_q_heads=w.n_q_heads,
+                        n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, block_size=B,
+                        max_position=w.pos_offset + T, rope_theta=w.rope_theta, rms_eps=w.rms_eps)
+    ctx = hc.Context(desc)
+    s = gh.stream_handle()
+    bt, num_pages = syn.block_table(w, w.pos_offset + T)
+    d_bt = gh.to_dev_i32(bt)
+    pos = (w.pos_offset + np.arange(T)).astype(np.int32)
+    n_chunks = (T + CT - 1) // CT
+    store = hc.Store(L, w.d_model, CT, L * n_chunks, pinned=True)
+    import os
+    with ThreadPoolExecutor(min(16, os.cpu_count() or 8)) as ex:                    # a different seeded input per layer
+        hidden = list(ex.map(lambda l: syn.layer_hidden(w, l), layers))
+    weights = [syn.layer_weights(w, l) for l in layers]
+    for i in range(L):
+        ctx.set_layer_weights(i, gh.to_dev_bf16(weights[i][0]), gh.to_dev_bf16(weights[i][1]), s)
+        torch.cuda.synchronize()
+    for c in range(n_chunks):                            # arrival order: chunk by chunk, layer by layer
+        for i in range(L):
+            rows = hidden[i][c * CT:(c + 1) * CT]
+            store.append(0, i, rows, len(rows))
+    print(f"{w.name}: {L} layers stored", flush=True)
+    copy_stream = torch.cuda.Stream()
+
+    def restore():
+        pools = [gh.new_pool(num_pages, B, w.n_kv_heads, w.head_dim) for _ in range(L)]
+        for i in range(L):
+            ctx.set_kv_pool(i, pools[i], num_pages)
+        ctx.restore_context(store, 0, 0, T, w.pos_offset, d_bt, len(bt), s, copy_stream.cuda_stream)
+        assert ctx.poll_device_error(s) == 0
+        torch.cuda.synchronize()
+        return pools
+
+    first = restore()
+    ctx.poison_staging(s)
+    second = restore()
+    for i in range(L):
+        assert torch.equal(first[i].view(torch.int16), second[i].view(torch.int16)), \
+            f"layer {layers[i]}: the restore after the staging buffers were poisoned differs"
+    del first
+    print(f"{w.name}: restored twice, staging poisoned in between", flush=True)
+    rng = np.random.default_rng([99, index])
+    edges = list(range(256, T, 256)) + list(range(CT, T, CT))
+    rows = sample_rows(rng, T, edges, range(0, B - w.pos_offset % B), range(T - 16, T))
+    for i, l in enumerate(layers):
+        res = check_layer(w, desc, gh.pool_bits(second[i]), hidden[i], weights[i][0], weights[i][1], pos,
+                          np.zeros(T, dtype=np.int64), bt[None, :], rows if l in sampled_layers else None,
+                          rng)
+        print(f"{w.name} layer {l}: sampled worst {res[0]:.3e} x RMS_head; projection check "
+              f"K {res[1]:.3f} V {res[2]:.3f} of limit", flush=True)
+        second[i] = None
+    ctx.destroy()
+    store.destroy()
 
 
 def test_ragged_workload(hc):

@@ -84,6 +84,9 @@ SHAPES = [
     (1024, 4, 128, 513, 1),
     (256, 1, 64, 1, 0),        # a single token, a single head
     (2048, 2, 128, 255, 0),
+    (64, 1, 64, 70, 0),        # fewer d_model steps (2) than the weight ring is deep (4)
+    (128, 2, 64, 300, 1),      # 4 steps: the ring is filled exactly once
+    (192, 1, 64, 33, 0),
 ]
 
 
