@@ -94,6 +94,14 @@ def main():
     ap.add_argument("--rope-style", type=int, default=None,
                     help="override the workload's RoPE convention (0 half-split, 1 interleaved, 2 none)")
     ap.add_argument("--loader", type=int, default=0, help="0 = copy engines, strided runs (default), 1 = gather kernel")
+    ap.add_argument("--chunk-tokens", type=int, default=None,
+                    help="tokens per chunk of the host store in the end-to-end leg (default: the workload's; "
+                         "the paper uses 64)")
+    ap.add_argument("--fragmented", action="store_true",
+                    help="end-to-end leg on a fragmented arena: eight contexts of the workload's length are "
+                         "appended in decode order (a few tokens at a time, taking turns), every other one is "
+                         "dropped, four new ones are appended into the holes, and the last of those is the one "
+                         "restored (single-context workloads only; needs 8x the pinned memory)")
     ap.add_argument("--zero-inputs", action="store_true",
                     help="diagnostic: all-zero hidden states and weights (same instruction stream, no "
                          "operand toggling) to show how far the matrix pipe's clock is power-limited")
@@ -247,8 +255,9 @@ def main():
     # ---- context: PCIe-inclusive end to end from the pinned chunk store (never `value`)
     e2e = None
     if not args.no_e2e:
-        CT = w.chunk_tokens
+        CT = args.chunk_tokens or w.chunk_tokens
         copy_stream = torch.cuda.Stream()
+        restored_seq, runs_per_layer = 0, None
         ctx.set_loader(args.loader)
         if ragged:
             # every context arrives as a prefill: chunk by chunk, layer by layer, context after context
@@ -265,14 +274,39 @@ def main():
                 ctx.restore_contexts(store, ids, lengths, d_bt, bt.shape[1], stream, copy_stream.cuda_stream)
         else:
             n_chunks = (T + CT - 1) // CT
-            store = hc.Store(L, d, CT, L * n_chunks, pinned=True)
-            for c in range(n_chunks):                      # arrival order: chunk by chunk, layer by layer
-                for l in range(L):
-                    rows = hidden_host[l][c * CT:(c + 1) * CT]
-                    store.append(0, l, rows, len(rows))
+
+            def feed(ids, piece):                          # decode order: contexts take turns
+                for a in range(0, T, piece):
+                    for sid in ids:
+                        for l in range(L):
+                            rows = hidden_host[l][a:a + piece]
+                            store.append(sid, l, rows, len(rows))
+
+            if args.fragmented:
+                store = hc.Store(L, d, CT, L * (8 * n_chunks + 8), pinned=True)
+                feed(range(8), 16)
+                for sid in (1, 3, 5, 7):
+                    store.drop(sid)
+                feed(range(10, 14), 16)
+                restored_seq = 13
+            else:
+                store = hc.Store(L, d, CT, L * n_chunks, pinned=True)
+                feed([0], CT)                              # arrival order: chunk by chunk, layer by layer
+            # copy-engine transfers per layer = runs of equally spaced chunks (from the index)
+            slots = np.array([store.chunk(restored_seq, 0, c)[0] for c in range(n_chunks)], dtype=np.int64)
+            runs_per_layer, c = 0, 0
+            while c < n_chunks:                            # as the loader groups them
+                e = c
+                if c + 1 < n_chunks and slots[c + 1] > slots[c]:
+                    stride = slots[c + 1] - slots[c]
+                    e = c + 1
+                    while e + 1 < n_chunks and slots[e + 1] - slots[e] == stride:
+                        e += 1
+                runs_per_layer += 1
+                c = e + 1
 
             def restore():
-                ctx.restore_context(store, 0, 0, T, w.pos_offset, d_bt, len(bt), stream,
+                ctx.restore_context(store, restored_seq, 0, T, w.pos_offset, d_bt, len(bt), stream,
                                     copy_stream.cuda_stream)
         for _ in range(2):
             restore()
@@ -298,6 +332,9 @@ def main():
         e2e = {"ms_per_restore": round(e2e_ms, 3), "tokens_per_s": round(T / (e2e_ms * 1e-3), 1),
                "host_link_GBps": round(host_bytes / (e2e_ms * 1e-3) / 1e9, 2),
                "plain_pinned_h2d_GBps": round(h2d_gbs, 2), "chunk_tokens": CT,
+               "arena": "fragmented (8 interleaved contexts, 4 dropped, 4 re-appended)" if args.fragmented
+               else "one context, arrival order",
+               "copy_transfers_per_layer": runs_per_layer,
                "loader": "copy engines, strided runs" if args.loader == 0 else "gather kernel",
                "note": "pinned chunk store -> loader on a side stream -> kernel, layer pipelined"}
         assert ctx.poll_device_error(stream) == 0

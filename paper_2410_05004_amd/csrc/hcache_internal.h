@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <map>
 #include <mutex>
 #include <string>
 #include <unordered_map>
@@ -194,20 +195,33 @@ struct hc_ctx {
 };
 
 struct hc_seq_state {
+  std::vector<int64_t> rows;                  // arena row of each chunk index (shared by all layers)
   std::vector<std::vector<int64_t>> chunks;   // per layer: arena chunk slots, in token order
   std::vector<int64_t> tokens;                // per layer: rows stored
 };
 
+// The arena is cut into ROWS of n_layers chunk slots: chunk index c of a context takes one row,
+// layer l's chunk sitting at slot row * n_layers + l.  A layer's chunks are therefore exactly
+// n_layers slots apart wherever the context's rows are consecutive, however the appends of
+// different contexts and layers interleave, and one strided transfer moves them all.  Rows are
+// handed out one at a time, with no reservation: a context continues right behind its last row
+// while that row is free; otherwise it starts a new run in the largest free extent -- at its
+// start, or in its middle when another context is growing into that extent from below (one
+// that took a row within the last kGrowthWindow allocations), so that contexts that arrive
+// interleaved each keep long runs of their own.
+constexpr int64_t kGrowthWindow = 64;
 struct hc_store {
   int32_t n_layers = 0, d_model = 0, chunk_tokens = 0;
   int64_t capacity_chunks = 0;
+  int64_t rows_total = 0, rows_free = 0;
   size_t row_bytes = 0, chunk_bytes = 0;
   unsigned char* arena = nullptr;
   bool pinned = false;
-  int64_t next_fresh = 0;                     // chunks [next_fresh, capacity) were never used
-  std::vector<int64_t> free_list;             // returned chunks, reused first
+  std::map<int64_t, int64_t> free_extents;    // first row -> number of rows, maximal and disjoint
+  std::unordered_map<int64_t, int64_t> growth;   // row behind a context's last row -> allocation count then
+  int64_t alloc_count = 0;                    // rows handed out so far
   std::unordered_map<int64_t, hc_seq_state> seqs;
-  // guards the index (seqs, free_list, next_fresh): appends, drops and the readers that copy
+  // guards the index (seqs, free_extents, growth): appends, drops and the readers that copy
   // chunk lists out of it may run on different threads; row payloads are copied outside of it
   mutable std::mutex index_mutex;
 };

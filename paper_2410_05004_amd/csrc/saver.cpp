@@ -30,6 +30,10 @@ using namespace hc;
 
 namespace {
 
+// rows of one context that fill at least this much of a chunk in one piece are copied from the
+// device straight into the arena; smaller pieces go through the snapshot slot and the daemons
+constexpr size_t kDirectMinBytes = 64 * 1024;
+
 struct SaveJob {
   int slot = -1;
   std::vector<StorePiece> pieces;    // where the rows go; src_off is relative to the slot
@@ -282,9 +286,48 @@ static hc_status save_layer_impl(hc_saver* sv, int32_t layer, const void* d_hidd
   };
   hipError_t e = hipEventRecord(sv->ev_ready[slot], cs);           // the layer's input is complete here
   if (e == hipSuccess) e = hipStreamWaitEvent(ds, sv->ev_ready[slot], 0);
-  if (e == hipSuccess)
-    e = hipMemcpyAsync(sv->slot_buf[slot], d_hidden, (size_t)n_rows * sv->row_bytes,
-                       hipMemcpyDeviceToHost, ds);                // ONE copy for the whole batch
+  // Long runs of one context's rows (a prefill, or the prefill share of a fused step) go
+  // straight from the device into their chunks of the pinned arena: no snapshot, no second
+  // copy by the daemons.  Full chunks of such a run sit a fixed distance apart in the arena, so
+  // they move in ONE strided transfer.  What is left -- the scattered single rows of decoding
+  // contexts -- is snapshot with one copy of the batch's sub-range that holds them and
+  // re-tiled by the daemon threads as before.
+  std::vector<StorePiece> small;
+  if (sv->store->pinned) {
+    const unsigned char* src = static_cast<const unsigned char*>(d_hidden);
+    std::vector<StorePiece>& pc = job->pieces;
+    size_t i = 0;
+    while (i < pc.size() && e == hipSuccess) {
+      if (pc[i].bytes < kDirectMinBytes) {
+        small.push_back(pc[i++]);
+        continue;
+      }
+      size_t j = i + 1;                                            // group [i, j): one strided transfer
+      if (j < pc.size() && pc[j].bytes == pc[i].bytes && pc[j].dst > pc[i].dst &&
+          pc[j].src_off == pc[i].src_off + pc[i].bytes) {
+        const size_t pitch = (size_t)(pc[j].dst - pc[i].dst);
+        ++j;
+        while (j < pc.size() && pc[j].bytes == pc[i].bytes && pc[j].dst == pc[j - 1].dst + pitch &&
+               pc[j].src_off == pc[j - 1].src_off + pc[i].bytes)
+          ++j;
+        e = hipMemcpy2DAsync(pc[i].dst, pitch, src + pc[i].src_off, pc[i].bytes, pc[i].bytes, j - i,
+                             hipMemcpyDeviceToHost, ds);
+      } else {
+        e = hipMemcpyAsync(pc[i].dst, src + pc[i].src_off, pc[i].bytes, hipMemcpyDeviceToHost, ds);
+      }
+      i = j;
+    }
+  } else {
+    small.swap(job->pieces);
+  }
+  if (e == hipSuccess && !small.empty()) {
+    // snapshot the sub-range of the batch that holds the remaining rows (pieces are in batch order)
+    const size_t lo = small.front().src_off, hi = small.back().src_off + small.back().bytes;
+    e = hipMemcpyAsync(sv->slot_buf[slot], static_cast<const unsigned char*>(d_hidden) + lo, hi - lo,
+                       hipMemcpyDeviceToHost, ds);
+    for (StorePiece& q : small) q.src_off -= lo;
+  }
+  job->pieces.swap(small);
   if (e == hipSuccess) e = hipEventRecord(sv->ev_copied[slot], ds);
   if (e == hipSuccess) {
     // a reused slot's event has just been re-recorded; keep it listed once

@@ -29,7 +29,14 @@ hc_status hc_store_create_ex(int32_t n_layers, int32_t d_model, int32_t chunk_to
   st->capacity_chunks = capacity_chunks;
   st->row_bytes = (size_t)d_model * 2;
   st->chunk_bytes = st->row_bytes * chunk_tokens;
-  const size_t bytes = st->chunk_bytes * (size_t)capacity_chunks;
+  st->rows_total = capacity_chunks / n_layers;           // whole arena rows (one chunk of every layer)
+  if (st->rows_total == 0) {
+    delete st;
+    return fail(HC_EINVAL, "capacity_chunks must be at least n_layers (one chunk of every layer)");
+  }
+  st->rows_free = st->rows_total;
+  st->free_extents[0] = st->rows_total;
+  const size_t bytes = st->chunk_bytes * (size_t)st->rows_total * (size_t)n_layers;
   if (pinned) {
     void* p = nullptr;
     hipError_t e = hipHostMalloc(&p, bytes, hipHostMallocDefault);
@@ -73,43 +80,96 @@ hc_status hc_store_destroy(hc_store* st) {
 
 namespace hc {
 
+// ---- arena rows (callers hold the index lock) ----------------------------------------------
+static void growth_add(hc_store* st, int64_t row) { st->growth[row] = st->alloc_count; }
+static void growth_del(hc_store* st, int64_t row) { st->growth.erase(row); }
+static bool growing_into(const hc_store* st, int64_t row) {
+  auto it = st->growth.find(row);
+  return it != st->growth.end() && st->alloc_count - it->second < kGrowthWindow;
+}
+
+// Take one row for a context whose last row is `last` (-1: none yet).
+static int64_t take_row(hc_store* st, int64_t last) {
+  int64_t row;
+  auto it = last >= 0 ? st->free_extents.find(last + 1) : st->free_extents.end();
+  if (it == st->free_extents.end()) {
+    // new run: the largest free extent; its start unless some context grows into it from below
+    it = st->free_extents.begin();
+    for (auto e = st->free_extents.begin(); e != st->free_extents.end(); ++e)
+      if (e->second > it->second) it = e;
+    if (growing_into(st, it->first) && it->second > 1) {
+      const int64_t start = it->first, len = it->second, mid = start + len / 2;
+      it->second = mid - start;                          // the lower half stays free
+      it = st->free_extents.emplace(mid, start + len - mid).first;
+    }
+  }
+  row = it->first;
+  const int64_t rest = it->second - 1;
+  st->free_extents.erase(it);
+  if (rest > 0) st->free_extents[row + 1] = rest;
+  --st->rows_free;
+  ++st->alloc_count;
+  if (last >= 0) growth_del(st, last + 1);
+  growth_add(st, row + 1);
+  return row;
+}
+
+static void give_row(hc_store* st, int64_t row) {
+  int64_t start = row, len = 1;
+  auto next = st->free_extents.find(row + 1);
+  if (next != st->free_extents.end()) {
+    len += next->second;
+    st->free_extents.erase(next);
+  }
+  auto prev = st->free_extents.lower_bound(row);
+  if (prev != st->free_extents.begin()) {
+    --prev;
+    if (prev->first + prev->second == row) {
+      start = prev->first;
+      len += prev->second;
+      st->free_extents.erase(prev);
+    }
+  }
+  st->free_extents[start] = len;
+  ++st->rows_free;
+}
+
 // Index half of an append: under the store's lock, check the order rule and the capacity, take
-// chunk slots and advance the token count of (seq_id, layer) by n_tok; report where the rows
+// arena rows and advance the token count of (seq_id, layer) by n_tok; report where the rows
 // go.  The caller copies the payload afterwards (no lock needed: the pieces are its own).
 hc_status store_reserve(hc_store* st, int64_t seq_id, int32_t layer, int32_t n_tok,
                         std::vector<StorePiece>& pieces) {
   std::lock_guard<std::mutex> lock(st->index_mutex);
   auto it = st->seqs.find(seq_id);
-  if (it == st->seqs.end()) {
+  const bool fresh_seq = it == st->seqs.end();
+  if (fresh_seq) {
     hc_seq_state fresh;
     fresh.chunks.resize(st->n_layers);
     fresh.tokens.assign(st->n_layers, 0);
     it = st->seqs.emplace(seq_id, std::move(fresh)).first;
   }
   hc_seq_state& s = it->second;
+  hc_status bad = HC_OK;
   // generation order: a layer never holds more tokens than the layer below it
   if (layer > 0 && s.tokens[layer - 1] < s.tokens[layer] + n_tok)
-    return fail(HC_ESTATE, "layer appended before the layer below it (layer-before-token order)");
+    bad = fail(HC_ESTATE, "layer appended before the layer below it (layer-before-token order)");
   // make sure the arena can take the whole append before touching anything
-  const int64_t have = (int64_t)s.chunks[layer].size() * st->chunk_tokens - s.tokens[layer];
-  const int64_t need_rows = n_tok > have ? n_tok - have : 0;
-  const int64_t need_chunks = (need_rows + st->chunk_tokens - 1) / st->chunk_tokens;
-  const int64_t avail = (int64_t)st->free_list.size() + (st->capacity_chunks - st->next_fresh);
-  if (need_chunks > avail) return fail(HC_ERANGE, "chunk arena is full");
+  const int64_t chunks_after = (s.tokens[layer] + n_tok + st->chunk_tokens - 1) / st->chunk_tokens;
+  const int64_t need_rows = chunks_after > (int64_t)s.rows.size() ? chunks_after - (int64_t)s.rows.size() : 0;
+  if (bad == HC_OK && need_rows > st->rows_free) bad = fail(HC_ERANGE, "chunk arena is full");
+  if (bad != HC_OK) {
+    if (fresh_seq) st->seqs.erase(it);                   // a failed first append leaves no trace
+    return bad;
+  }
 
   size_t src_off = 0;
   int32_t left = n_tok;
   while (left > 0) {
     const int64_t fill = s.tokens[layer] % st->chunk_tokens;
     if (fill == 0 && s.tokens[layer] == (int64_t)s.chunks[layer].size() * st->chunk_tokens) {
-      int64_t slot;
-      if (!st->free_list.empty()) {
-        slot = st->free_list.back();
-        st->free_list.pop_back();
-      } else {
-        slot = st->next_fresh++;
-      }
-      s.chunks[layer].push_back(slot);
+      const size_t c = s.chunks[layer].size();           // chunk index this layer starts
+      if (c >= s.rows.size()) s.rows.push_back(take_row(st, s.rows.empty() ? -1 : s.rows.back()));
+      s.chunks[layer].push_back(s.rows[c] * st->n_layers + layer);
     }
     const int64_t room = st->chunk_tokens - fill;
     const int32_t take = left < room ? left : (int32_t)room;
@@ -175,8 +235,8 @@ hc_status hc_store_drop(hc_store* st, int64_t seq_id) {
   std::lock_guard<std::mutex> lock(st->index_mutex);
   auto it = st->seqs.find(seq_id);
   if (it == st->seqs.end()) return fail(HC_ERANGE, "unknown context");
-  for (auto& per_layer : it->second.chunks)
-    for (int64_t slot : per_layer) st->free_list.push_back(slot);
+  if (!it->second.rows.empty()) hc::growth_del(st, it->second.rows.back() + 1);
+  for (int64_t row : it->second.rows) hc::give_row(st, row);
   st->seqs.erase(it);
   return HC_OK;
 }

@@ -54,6 +54,35 @@ def run(hc, torch, w, rows_per_step, n_ctx, steps, threads, chunk_tokens):
             "producer_blocked_fraction": round(t_enq / dt, 3)}
 
 
+def run_fused(hc, torch, w, prefill_rows, decode_ctx, steps, threads, chunk_tokens):
+    """A fused step: a prefill chunk of one context plus one row each of `decode_ctx` others."""
+    L, d = w.n_layers, w.d_model
+    rows = prefill_rows + decode_ctx
+    cap = L * (-(-prefill_rows * steps // chunk_tokens) + decode_ctx * (-(-steps // chunk_tokens)) + 8)
+    store = hc.Store(L, d, chunk_tokens, cap, pinned=True)
+    saver = hc.Saver(store, rows, n_slots=8, n_threads=threads)
+    act = torch.randn((rows, d), device="cuda").to(torch.bfloat16)
+    row_seq = np.concatenate([np.zeros(prefill_rows), 1 + np.arange(decode_ctx)]).astype(np.int64)
+    compute = torch.cuda.current_stream().cuda_stream
+    down = torch.cuda.Stream()
+    for l in range(L):
+        saver.save_layer(l, act, rows, row_seq, compute, down.cuda_stream)
+    saver.flush()
+    t0 = time.perf_counter()
+    for _ in range(steps - 1):
+        for l in range(L):
+            saver.save_layer(l, act, rows, row_seq, compute, down.cuda_stream)
+    saver.flush()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    nbytes = (steps - 1) * L * rows * d * 2
+    saver.destroy()
+    store.destroy()
+    return {"rows_per_step": rows, "prefill_rows": prefill_rows, "decode_contexts": decode_ctx,
+            "steps": steps - 1, "GBps": round(nbytes / dt / 1e9, 2),
+            "ms_per_layer": round(dt * 1e3 / ((steps - 1) * L), 4)}
+
+
 def overlap(hc, torch, w, rows, steps, threads, chunk_tokens):
     """Cost of saving on the compute stream: a stand-in for one layer's forward compute (12
     [rows, d] x [d, d] products = the 24 N D^2 flop of a layer) runs per layer, (a) alone,
@@ -100,6 +129,20 @@ def overlap(hc, torch, w, rows, steps, threads, chunk_tokens):
     return {"rows_per_step": rows, "steps": steps, "ms_per_step_all_layers": res}
 
 
+def d2h_rate(torch, nbytes=64 << 20, reps=10):
+    """Plain pinned device->host copy rate of the box (one large block), GB/s."""
+    src = torch.empty(nbytes // 2, dtype=torch.int16, device="cuda")
+    dst = torch.empty(nbytes // 2, dtype=torch.int16).pin_memory()
+    for _ in range(2):
+        dst.copy_(src, non_blocking=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        dst.copy_(src, non_blocking=True)
+    torch.cuda.synchronize()
+    return reps * nbytes / (time.perf_counter() - t0) / 1e9
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", type=int, default=3)
@@ -111,10 +154,12 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("save_rate: no GPU visible")
     w = syn.WORKLOADS[args.workload]
+    link = d2h_rate(torch)
     out = {"workload": w.name, "d_model": w.d_model, "layers": w.n_layers, "threads": args.threads,
-           "paper_required_GBps": 3.0,
+           "paper_required_GBps": 3.0, "plain_pinned_d2h_GBps": round(link, 2),
            "prefill": run(hc, torch, w, 1024, 1, 9, args.threads, 64),
            "decode": run(hc, torch, w, 64, 64, 65, args.threads, 64),
+           "fused": run_fused(hc, torch, w, 960, 64, 9, args.threads, 64),
            "beside_compute": overlap(hc, torch, w, 1024, 4, args.threads, 64)}
     print(json.dumps(out))
 

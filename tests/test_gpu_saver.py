@@ -123,7 +123,7 @@ def test_saver_at_13b_width(hc):
     L, d_model, CT = 3, 5120, 64
     rng = np.random.default_rng(13)
     n_ctx, prefill, decode_steps = 48, 1024, 5
-    store = hc.Store(L, d_model, CT, L * ((prefill + CT - 1) // CT + n_ctx) + n_ctx * L + 8, pinned=True)
+    store = hc.Store(L, d_model, CT, L * ((prefill + CT - 1) // CT + n_ctx) + n_ctx * L + 8 + 12 * L, pinned=True)
     saver = hc.Saver(store, 1024, n_slots=4, n_threads=8)
     ref = oracle.ChunkStore(L, d_model, CT)
     compute = torch.cuda.current_stream()
@@ -146,8 +146,15 @@ def test_saver_at_13b_width(hc):
     ids = np.array([100] + list(range(1, n_ctx)), dtype=np.int64)
     for _ in range(decode_steps):
         save_step(ids, [rng.integers(0, 1 << 16, size=(n_ctx, d_model), dtype=np.uint16) for _ in range(L)])
+    # fused steps (chunked prefill sharing a batch with decode rows): long runs of contexts 200
+    # and 201 go from the device straight into their chunks (full chunks in one strided
+    # transfer, the partial ones at either end on their own; the second step starts mid-chunk),
+    # the single rows in between through the snapshot slot and the daemon threads
+    for n200, n201 in ((300, 100), (200, 70)):
+        ids = np.concatenate([np.full(n200, 200), np.arange(1, 11), np.full(n201, 201)]).astype(np.int64)
+        save_step(ids, [rng.integers(0, 1 << 16, size=(len(ids), d_model), dtype=np.uint16) for _ in range(L)])
     saver.flush()
-    for sid in (100, 1, n_ctx - 1):
+    for sid in (100, 1, n_ctx - 1, 200, 201, 10):
         for l in range(L):
             assert store.tokens(sid, l) == ref.n_tokens(sid, l)
             for c in range(ref.n_chunks(sid, l)):

@@ -89,11 +89,15 @@ def test_store_matches_oracle_model(hc):
         assert e.value.status == hc.HC_ERANGE
     # Figure 6: 2nd token, 2nd layer -> chunk (layer 1, 0), row 1
     assert np.array_equal(read_chunk(st, 7, 1, 0, d)[1], full[1, 1])
-    # chunks are taken from the arena in arrival order: the 5-token prefill fills two
-    # chunks of layer 0, then two of layer 1, then two of layer 2
-    p = [st.chunk(7, l, 0)[0] for l in range(L)]
-    assert p[1] - p[0] == 2 * CT * d * 2 and p[2] - p[1] == 2 * CT * d * 2
-    assert st.chunk(7, 0, 1)[0] - p[0] == CT * d * 2
+    # the arena is cut into rows of L chunk slots: chunk index c of every layer shares a row
+    # (layer l at slot l of it), and a context's rows are consecutive while nothing interferes,
+    # so a layer's chunks are exactly L slots apart -- one strided transfer per layer
+    chunk_bytes = CT * d * 2
+    p = [[st.chunk(7, l, c)[0] for c in range(3)] for l in range(L)]
+    for c in range(3):
+        assert p[1][c] - p[0][c] == chunk_bytes and p[2][c] - p[1][c] == chunk_bytes
+    for l in range(L):
+        assert p[l][1] - p[l][0] == L * chunk_bytes and p[l][2] - p[l][1] == L * chunk_bytes
     st.destroy()
 
 
@@ -121,6 +125,42 @@ def test_store_errors_and_reuse(hc):
     assert st.tokens(2, 0) == 5
     assert st.chunk(2, 0, 1)[1] == 1                # tail chunk holds one row
     st.append(2, 0, rows, 0)                        # empty append is a no-op
+    st.destroy()
+
+
+def test_store_rows_stay_regular_under_interleaving_and_reuse(hc):
+    """Four contexts appended in decode order (a few tokens at a time, taking turns), two of
+    them dropped, two new ones appended into the holes: every context's chunks of a layer stay
+    L slots apart in long runs (the spacing the strided loader needs), and every byte reads back."""
+    L, d, CT, T = 4, 8, 4, 96
+    n_idx = T // CT
+    st = hc.Store(L, d, CT, capacity_chunks=L * (4 * n_idx + 8), pinned=False)
+    rng = np.random.default_rng(4)
+    data = {s: rng.integers(0, 65536, size=(L, T, d), dtype=np.uint16) for s in (1, 2, 3, 4, 5, 6)}
+
+    def feed(ids):
+        for a in range(0, T, 3):
+            for s in ids:
+                for l in range(L):
+                    st.append(s, l, np.ascontiguousarray(data[s][l, a:a + 3]), 3)
+
+    def runs(s, l):
+        slots = [(st.chunk(s, l, c)[0] - st.chunk(1, 0, 0)[0]) // (CT * d * 2) for c in range(n_idx)]
+        gaps = np.diff(slots)
+        assert all((slots[c] - l) % L == 0 for c in range(n_idx))       # slot l of a row
+        return 1 + int(np.sum(gaps != L))
+
+    feed((1, 2, 3, 4))
+    for s in (1, 2, 3, 4):
+        assert max(runs(s, l) for l in range(L)) <= 3, "interleaved arrivals broke a context into many runs"
+    st.drop(2)
+    st.drop(4)
+    feed((5, 6))
+    for s in (1, 3, 5, 6):
+        assert max(runs(s, l) for l in range(L)) <= 4
+        for l in range(L):
+            got = np.concatenate([read_chunk(st, s, l, c, d) for c in range(n_idx)])
+            assert np.array_equal(got, data[s][l])
     st.destroy()
 
 
