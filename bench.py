@@ -105,6 +105,12 @@ def main():
     ap.add_argument("--zero-inputs", action="store_true",
                     help="diagnostic: all-zero hidden states and weights (same instruction stream, no "
                          "operand toggling) to show how far the matrix pipe's clock is power-limited")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="context: also time the vendor library's plain bf16 GEMM (torch.mm = hipBLASLt) on the "
+                         "same hidden states and unpacked weights, layer after layer, no norm / RoPE / paging")
+    ap.add_argument("--power-probe", action="store_true",
+                    help="diagnostic: run the matrix-pipe duty-cycle probe (hc_diag_mfma_duty) instead of the "
+                         "benchmark and print its table as one JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB -> 256 MiB streaming kernel three times, so that a "
                          "counter run has a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
@@ -119,6 +125,20 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the restoration path has no CPU fallback")
+    if args.power_probe:
+        torch.cuda.set_device(0)
+        rows = []
+        for period_us, duty, half in ((1000, 1.0, False), (200, 0.5, False), (1000, 0.5, False),
+                                      (10000, 0.5, False), (1000, 0.25, False), (1000, 0.5, True),
+                                      (10000, 0.5, True)):
+            rows.append({"period_us": period_us, "duty": duty, "half_of_the_cus_at_a_time": half,
+                         "tflops_inside_busy_windows": round(hc.diag_mfma_duty(period_us, duty, half), 1)})
+            log(rows[-1])
+        zero = round(hc.diag_mfma_duty(1000, 1.0, False, zero_operands=True), 1)
+        print(json.dumps({"probe": "mfma duty cycle, random bf16 operands in registers, 32x32x16",
+                          "rows": rows, "continuous_zero_operands_tflops": zero,
+                          "peak_tflops": MFMA_BF16_PEAK_TFLOPS}), flush=True)
+        return
     w = syn.WORKLOADS[args.workload]
     ragged = w.n_seq != 1
     dev = torch.device("cuda:0")
@@ -153,7 +173,7 @@ def main():
         bt, num_pages = syn.block_table(w, w.pos_offset + T)
         d_bt = torch.from_numpy(bt).to(dev)
         d_pos = torch.arange(w.pos_offset, w.pos_offset + T, dtype=torch.int32, device=dev)
-    pools, hidden_dev, hidden_host = [], [], []
+    pools, hidden_dev, hidden_host, raw_weights = [], [], [], []
     def generate(l):
         return syn.layer_weights(w, l), syn.layer_hidden(w, l, T)
     workers = min(8, os.cpu_count() or 8)                  # a few layers at a time: bounded host memory
@@ -174,6 +194,8 @@ def main():
         else:
             ctx.set_layer_weights(l, d_w, d_g, stream)
         torch.cuda.synchronize()
+        if args.vendor_gemm:
+            raw_weights.append(d_w)
         del d_w, d_g
         pool = torch.zeros((num_pages, 2, w.block_size, w.n_kv_heads, w.head_dim),
                            dtype=torch.bfloat16, device=dev)
@@ -251,6 +273,27 @@ def main():
                 "layers_per_launch": round(layers_per_launch, 2),
                 "flop_per_launch": flop_per_launch}
     assert ctx.poll_device_error(stream) == 0
+
+    # ---- context: the vendor library's plain GEMM on the same operands
+    vendor = None
+    if args.vendor_gemm:
+        out_buf = torch.empty((T, 2 * w.d_kv), dtype=torch.bfloat16, device=dev)
+        for l in range(L):
+            torch.mm(hidden_dev[l], raw_weights[l].t(), out=out_buf)
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = max(1, min(args.steps, 50))
+        ev0.record()
+        for _ in range(reps):
+            for l in range(L):
+                torch.mm(hidden_dev[l], raw_weights[l].t(), out=out_buf)
+        ev1.record()
+        torch.cuda.synchronize()
+        us = ev0.elapsed_time(ev1) * 1e3 / (reps * L)
+        vendor = {"us_per_layer": round(us, 2), "TFLOPs": round(4.0 * T * d * w.d_kv / us / 1e6, 1),
+                  "note": "torch.mm (hipBLASLt), bf16, row-major output, no normalisation, RoPE or paging; "
+                          "back-to-back launches between one pair of events"}
+        del out_buf
 
     # ---- context: PCIe-inclusive end to end from the pinned chunk store (never `value`)
     e2e = None
@@ -368,6 +411,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "e2e_host_link": e2e,
+        "vendor_gemm": vendor,
         "paper_context": "paper reports ratios only: TTFT up to 1.93x vs KV offload and 5.73x vs "
                          "recomputation on A100-40G, fp16 (Section 6); no absolute tokens/s",
     }

@@ -386,6 +386,16 @@ hc_status hc_timing_end(hc_ctx* ctx, void* stream, double* out_avg_ms, int32_t* 
 hc_status hc_timing_end_stats(hc_ctx* ctx, void* stream, double* out_avg_ms, double* out_min_ms,
                               double* out_median_ms, int32_t* out_launches);
 
+/* Matrix-pipe duty-cycle probe (measurement only; evidence for how the chip's power management
+ * bounds the restoration kernel).  All compute units run bursts of bf16 matrix ops on register
+ * operands, busy while (wall clock mod period_us) < duty * period_us and asleep otherwise, for
+ * total_us; with half_phase != 0 every other workgroup is busy in the other half of the period
+ * (so half the chip is idle at any moment).  *out_tflops = matrix-op rate inside the busy
+ * windows, scaled to the whole chip.  zero_operands != 0 uses all-zero operands (no operand
+ * toggling).  Allocates and frees small device buffers, synchronises the device. */
+hc_status hc_diag_mfma_duty(double period_us, double duty, int32_t half_phase, double total_us,
+                            int32_t zero_operands, double* out_tflops);
+
 #ifdef __cplusplus
 }
 #endif

@@ -3,7 +3,8 @@ import ctypes as C
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_FILE = os.path.join(HERE, "libhcache.so")
+# HCACHE_LIB names another build of the library (the diagnostic variants of build.py --diag)
+_LIB_FILE = os.environ.get("HCACHE_LIB") or os.path.join(HERE, "libhcache.so")
 
 HC_OK, HC_EINVAL, HC_ERANGE, HC_EALIGN, HC_ENOMEM, HC_EHIP, HC_ESTATE = 0, -1, -2, -3, -4, -5, -6
 HC_DEV_BAD_POSITION, HC_DEV_BAD_PAGE = 1, 2
@@ -86,6 +87,7 @@ def _load():
         "hc_saver_fence": (i32, [vp, vp]),
         "hc_saver_save_layer_host": (i32, [vp, i32, vp, i32, vp]),
         "hc_saver_flush": (i32, [vp]),
+        "hc_diag_mfma_duty": (i32, [C.c_double, C.c_double, i32, C.c_double, i32, p(C.c_double)]),
         "hc_timing_begin": (i32, [vp]),
         "hc_timing_end": (i32, [vp, vp, p(C.c_double), p(i32)]),
         "hc_timing_end_stats": (i32, [vp, vp, p(C.c_double), p(C.c_double), p(C.c_double), p(i32)]),
@@ -105,7 +107,7 @@ EXPORTED = ("hc_last_error hc_version hc_validate_desc hc_create hc_destroy hc_s
             "hc_saver_flush hc_partition_layers hc_gather_kv hc_scatter_kv "
             "hc_restore_context_mixed hc_set_layer_weights_affine hc_saver_save_layer_deferred "
             "hc_saver_fence hc_restore_kv_layers hc_restore_contexts hc_timing_end_stats "
-            "hc_restore_context_static hc_static_stage_bytes hc_poison_staging").split()
+            "hc_restore_context_static hc_static_stage_bytes hc_poison_staging hc_diag_mfma_duty").split()
 
 
 def _check(status):
@@ -115,6 +117,14 @@ def _check(status):
 
 def static_stage_bytes():
     return lib.hc_static_stage_bytes()
+
+
+def diag_mfma_duty(period_us, duty, half_phase=False, total_us=60000.0, zero_operands=False):
+    """Matrix-op rate (TFLOP/s, whole chip) inside the busy windows of a duty-cycled burst."""
+    out = C.c_double(0)
+    _check(lib.hc_diag_mfma_duty(period_us, duty, 1 if half_phase else 0, total_us,
+                                 1 if zero_operands else 0, C.byref(out)))
+    return out.value
 
 
 def version():

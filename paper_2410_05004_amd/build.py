@@ -19,11 +19,19 @@ def hipcc_path():
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose=False, extra_flags=()):
+# Diagnostic builds: each name takes one companion of the matrix ops out of the restoration
+# kernel's main loop (results are then wrong on purpose; timing only).  `--diag NAME[,NAME]`
+# writes libhcache_diag_<names>.so next to the library; HCACHE_LIB=<path> makes the binding
+# load it instead.
+DIAG = {"no_sumsq": "-DHC_DIAG_NO_SUMSQ", "no_loads": "-DHC_DIAG_NO_LOADS",
+        "no_ldsread": "-DHC_DIAG_NO_LDSREAD", "no_barrier": "-DHC_DIAG_NO_BARRIER"}
+
+
+def build(verbose=False, extra_flags=(), out=None, tag=""):
     """Compile every source for gfx950 (one hipcc process per file, in parallel) and link the
-    shared library.  Always recompiles."""
+    shared library (`out`, default libhcache.so next to this file).  Always recompiles."""
     from concurrent.futures import ThreadPoolExecutor
-    obj_dir = os.path.join(HERE, "_build")
+    obj_dir = os.path.join(HERE, "_build" + tag)
     os.makedirs(obj_dir, exist_ok=True)
     common = [
         hipcc_path(), "-x", "hip", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -51,15 +59,25 @@ def build(verbose=False, extra_flags=()):
         for _, r in results:
             sys.stderr.write(r.stderr)
     link = [hipcc_path(), "--offload-arch=gfx950", "-shared", "-fPIC", "-pthread",
-            *[o for o, _ in results], "-o", LIB]
+            *[o for o, _ in results], "-o", out or LIB]
     if verbose:
         print(" ".join(link), flush=True)
     res = subprocess.run(link, capture_output=True, text=True)
     if res.returncode != 0:
         sys.stderr.write(res.stdout + res.stderr)
         raise RuntimeError("link failed")
-    return LIB
+    return out or LIB
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import argparse
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--diag", default="", help="comma-separated diagnostic variants: " + ", ".join(DIAG))
+    a = ap.parse_args()
+    if a.diag:
+        names = a.diag.split(",")
+        print(build(verbose=True, extra_flags=tuple(DIAG[n] for n in names),
+                    out=os.path.join(HERE, "libhcache_diag_" + "_".join(names) + ".so"),
+                    tag="_diag_" + "_".join(names)))
+    else:
+        print(build(verbose=True))

@@ -227,4 +227,106 @@ hipError_t launch_kv_rows(const KvRowsArgs& a, bool to_pool, hipStream_t stream)
   return hipGetLastError();
 }
 
+// ---- matrix-pipe duty-cycle probe (measurement only) -----------------------------------------
+// Every CU runs bursts of v_mfma_f32_32x32x16_bf16 on register operands (eight waves, two per
+// SIMD, eight accumulator blocks each) gated by the constant-rate wall clock: busy while
+// (t mod period) < busy, asleep otherwise; with `half_phase` odd workgroups are busy in the
+// other half of the period.  The matrix ops issued inside the busy windows are counted.
+// If the chip's power management averaged over time, a 50 % duty cycle would let the busy
+// windows run faster than a continuous run; if it follows the instantaneous activity of the
+// whole chip, they run at the continuous rate -- and faster only when half the CUs are idle at
+// any moment.
+typedef __attribute__((ext_vector_type(8))) __bf16 probe_bf16x8;
+typedef __attribute__((ext_vector_type(16))) float probe_f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t probe_u32x4;
+
+__global__ __launch_bounds__(512) void mfma_duty_kernel(const probe_u32x4* __restrict__ ops,
+                                                        float* __restrict__ sink,
+                                                        unsigned long long period_ticks,
+                                                        unsigned long long busy_ticks,
+                                                        unsigned long long total_ticks, int half_phase,
+                                                        unsigned long long* __restrict__ batches_out) {
+  probe_f32x16 acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+  probe_bf16x8 a[4], b[2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) a[i] = __builtin_bit_cast(probe_bf16x8, ops[(threadIdx.x * 8 + i) & 2047]);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) b[i] = __builtin_bit_cast(probe_bf16x8, ops[(threadIdx.x * 8 + 4 + i) & 2047]);
+  const unsigned long long t_begin = wall_clock64();      // 100 MHz
+  const unsigned long long phase = (half_phase && (blockIdx.x & 1)) ? period_ticks / 2 : 0;
+  unsigned long long batches = 0;
+  for (;;) {                                              // every wave leaves after total_ticks
+    const unsigned long long t = wall_clock64();
+    if (t - t_begin >= total_ticks) break;
+    if (((t + phase) % period_ticks) < busy_ticks) {
+      for (int it = 0; it < 4; ++it) {                    // one batch = 32 matrix ops per wave
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[i * 2 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i * 2 + j], 0, 0, 0);
+      }
+      ++batches;
+    } else {
+      __builtin_amdgcn_s_sleep(32);
+    }
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s += acc[i][v];
+  sink[blockIdx.x * blockDim.x + threadIdx.x] = s;
+  if ((threadIdx.x & 63) == 0) batches_out[blockIdx.x * 8 + (threadIdx.x >> 6)] = batches;
+}
+
+hipError_t run_mfma_duty(double period_us, double duty, int half_phase, double total_us,
+                         int zero_operands, double* out_tflops) {
+  const int n_wg = 256, n_waves = n_wg * 8;
+  probe_u32x4* ops = nullptr;
+  float* sink = nullptr;
+  unsigned long long* batches = nullptr;
+  std::vector<uint32_t> h(2048 * 4);
+  uint32_t x = 0x9E3779B9u;                               // xorshift: random signs and mantissas,
+  for (uint32_t& w : h) {                                 // exponents of values near 1
+    uint32_t halves[2];
+    for (uint32_t& half : halves) {
+      x ^= x << 13; x ^= x >> 17; x ^= x << 5;
+      half = (x & 0x807Fu) | ((0x7Eu + (x >> 20) % 3u) << 7);
+    }
+    w = zero_operands ? 0u : (halves[1] << 16) | halves[0];
+  }
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&ops), h.size() * 4);
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&sink), (size_t)n_wg * 512 * 4);
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&batches), (size_t)n_waves * 8);
+  if (e == hipSuccess) e = hipMemcpy(ops, h.data(), h.size() * 4, hipMemcpyHostToDevice);
+  std::vector<unsigned long long> hb(n_waves);
+  if (e == hipSuccess) {
+    const unsigned long long P = (unsigned long long)(period_us * 100.0);
+    const unsigned long long B = (unsigned long long)(period_us * 100.0 * duty);
+    const unsigned long long T = (unsigned long long)(total_us * 100.0);
+    for (int rep = 0; rep < 2 && e == hipSuccess; ++rep) {   // the first run warms up
+      hipLaunchKernelGGL(mfma_duty_kernel, dim3(n_wg), dim3(512), 0, nullptr, ops, sink, P ? P : 1, B, T,
+                         half_phase, batches);
+      e = hipGetLastError();
+      if (e == hipSuccess) e = hipDeviceSynchronize();
+    }
+    if (e == hipSuccess) e = hipMemcpy(hb.data(), batches, hb.size() * 8, hipMemcpyDeviceToHost);
+  }
+  if (e == hipSuccess) {
+    double n = 0;
+    for (unsigned long long v : hb) n += (double)v;
+    // flop issued inside busy windows / time the windows were open (per CU: duty * total)
+    *out_tflops = n * 32.0 * 32768.0 / (duty * total_us * 1e-6) / 1e12;
+  }
+  if (ops) (void)hipFree(ops);
+  if (sink) (void)hipFree(sink);
+  if (batches) (void)hipFree(batches);
+  return e;
+}
+
 }  // namespace hc

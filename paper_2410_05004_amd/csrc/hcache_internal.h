@@ -44,7 +44,7 @@ struct RestoreArgs {
   const float2* rope;            // [max_position][head_dim/2] (cos, sin); unused when rope_style = 2
   const float2* affine;          // [n_phys] per packed row: (sum of the row, constant term); modes 1, 2
   uint16_t* pool;                // bf16 [num_pages][2][block_size][n_kv_heads][head_dim]
-  int32_t* err;                  // sticky error word (device-visible host memory)
+  int32_t* err;                  // sticky error word
   int64_t num_pages;
   int32_t pos_base;
   int32_t n_seq;
@@ -95,6 +95,11 @@ hipError_t launch_pack_affine(const uint16_t* wkv, const uint16_t* gamma, const 
 hipError_t launch_rope_table(float2* table, int max_position, int head_dim, double theta,
                              hipStream_t stream);
 hipError_t configure_kernels();   // one-time function attributes (dynamic LDS size)
+// Measurement only: chip-wide matrix-op rate (TFLOP/s, as if all 256 CUs were busy) inside
+// the busy windows of a duty-cycled burst pattern; allocates and frees its own buffers and
+// synchronises the device.
+hipError_t run_mfma_duty(double period_us, double duty, int half_phase, double total_us,
+                         int zero_operands, double* out_tflops);
 
 // One contiguous piece of a layer's hidden states in the host store and where it goes in
 // the HBM staging buffer.  `bytes` is a multiple of 16.
@@ -166,8 +171,7 @@ struct hc_ctx {
   int device = 0;
   int d_kv = 0, d_kv_pad = 0, n_phys = 0, block_shift = 0;
   float2* rope = nullptr;                 // owned, device
-  int32_t* err_host = nullptr;            // owned, pinned + mapped
-  int32_t* err_dev = nullptr;             // device view of err_host
+  int32_t* err_dev = nullptr;             // owned, device: sticky error word
   std::vector<hc_layer_state> layers;
   // staging for hc_restore_context
   uint16_t* stage[2] = {nullptr, nullptr};
