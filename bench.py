@@ -105,6 +105,9 @@ def main():
     ap.add_argument("--zero-inputs", action="store_true",
                     help="diagnostic: all-zero hidden states and weights (same instruction stream, no "
                          "operand toggling) to show how far the matrix pipe's clock is power-limited")
+    ap.add_argument("--d-model", type=int, default=None,
+                    help="diagnostic: override the workload's d_model (a multiple of 64) to separate the cost "
+                         "per channel from the fixed cost per tile; implies a different synthetic shape")
     ap.add_argument("--vendor-gemm", action="store_true",
                     help="context: also time the vendor library's plain bf16 GEMM (torch.mm = hipBLASLt) on the "
                          "same hidden states and unpacked weights, layer after layer, no norm / RoPE / paging")
@@ -140,6 +143,9 @@ def main():
                           "peak_tflops": MFMA_BF16_PEAK_TFLOPS}), flush=True)
         return
     w = syn.WORKLOADS[args.workload]
+    if args.d_model:
+        import dataclasses
+        w = dataclasses.replace(w, d_model=args.d_model, name=f"{w.name}-d{args.d_model}")
     ragged = w.n_seq != 1
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
