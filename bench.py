@@ -138,8 +138,12 @@ def main():
                          "tflops_inside_busy_windows": round(hc.diag_mfma_duty(period_us, duty, half), 1)})
             log(rows[-1])
         zero = round(hc.diag_mfma_duty(1000, 1.0, False, zero_operands=True), 1)
+        other = round(hc.diag_mfma_duty(1000, 1.0, False, op_shape=1), 1)
+        other_zero = round(hc.diag_mfma_duty(1000, 1.0, False, zero_operands=True, op_shape=1), 1)
         print(json.dumps({"probe": "mfma duty cycle, random bf16 operands in registers, 32x32x16",
                           "rows": rows, "continuous_zero_operands_tflops": zero,
+                          "continuous_16x16x32_tflops": other,
+                          "continuous_16x16x32_zero_operands_tflops": other_zero,
                           "peak_tflops": MFMA_BF16_PEAK_TFLOPS}), flush=True)
         return
     w = syn.WORKLOADS[args.workload]

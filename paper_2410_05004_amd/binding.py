@@ -87,7 +87,7 @@ def _load():
         "hc_saver_fence": (i32, [vp, vp]),
         "hc_saver_save_layer_host": (i32, [vp, i32, vp, i32, vp]),
         "hc_saver_flush": (i32, [vp]),
-        "hc_diag_mfma_duty": (i32, [C.c_double, C.c_double, i32, C.c_double, i32, p(C.c_double)]),
+        "hc_diag_mfma_duty": (i32, [C.c_double, C.c_double, i32, C.c_double, i32, i32, p(C.c_double)]),
         "hc_timing_begin": (i32, [vp]),
         "hc_timing_end": (i32, [vp, vp, p(C.c_double), p(i32)]),
         "hc_timing_end_stats": (i32, [vp, vp, p(C.c_double), p(C.c_double), p(C.c_double), p(i32)]),
@@ -119,11 +119,11 @@ def static_stage_bytes():
     return lib.hc_static_stage_bytes()
 
 
-def diag_mfma_duty(period_us, duty, half_phase=False, total_us=60000.0, zero_operands=False):
+def diag_mfma_duty(period_us, duty, half_phase=False, total_us=60000.0, zero_operands=False, op_shape=0):
     """Matrix-op rate (TFLOP/s, whole chip) inside the busy windows of a duty-cycled burst."""
     out = C.c_double(0)
     _check(lib.hc_diag_mfma_duty(period_us, duty, 1 if half_phase else 0, total_us,
-                                 1 if zero_operands else 0, C.byref(out)))
+                                 1 if zero_operands else 0, op_shape, C.byref(out)))
     return out.value
 
 

@@ -449,12 +449,13 @@ hc_status hc_set_loader(hc_ctx* ctx, int32_t mode) {
 }
 
 hc_status hc_diag_mfma_duty(double period_us, double duty, int32_t half_phase, double total_us,
-                            int32_t zero_operands, double* out_tflops) {
+                            int32_t zero_operands, int32_t op_shape, double* out_tflops) {
   clear_error();
   if (!out_tflops) return fail(HC_EINVAL, "null output pointer");
+  if (op_shape != 0 && op_shape != 1) return fail(HC_EINVAL, "op_shape: 0 (32x32x16) or 1 (16x16x32)");
   if (!(period_us >= 1.0) || !(duty > 0.0) || !(duty <= 1.0) || !(total_us >= period_us) || total_us > 2e6)
     return fail(HC_EINVAL, "period_us >= 1, 0 < duty <= 1, period_us <= total_us <= 2e6");
-  HC_HIP(run_mfma_duty(period_us, duty, half_phase, total_us, zero_operands, out_tflops));
+  HC_HIP(run_mfma_duty(period_us, duty, half_phase, total_us, zero_operands, op_shape, out_tflops));
   return HC_OK;
 }
 

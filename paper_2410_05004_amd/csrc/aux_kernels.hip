@@ -13,10 +13,10 @@ namespace hc {
 //   groups at or beyond d_kv / 64 are zero padding.  The first 32 rows of a group are the
 //   first members of those pairs, the last 32 rows the second members (half-split: features
 //   i and i + hd/2; interleaved: features 2i and 2i + 1; V rows use the same order);
-//   inside a 32-row block, row i maps to pair offset u = 16*((i/4)%2) + 4*(i/8) + i%4,
-//   which is the order in which a lane of v_mfma_f32_32x32x16 receives its 16 outputs
-//   (register v of lane half g holds block row 8*(v/4) + 4*g + v%4), so that a lane ends
-//   up with 16 consecutive pair offsets.
+//   inside a 32-row block (two 16-row matrix-op blocks), row i maps to pair offset
+//   u = 8*((i/4)%4) + 4*(i/16) + i%4: register v of lane quarter q of v_mfma_f32_16x16x32
+//   holds block row 4*q + v, so a lane's registers of the two blocks are the 8 consecutive
+//   pair offsets 8*q .. 8*q + 7 (one 16-byte store).
 // Value: bf16( float(W[logical row][c]) * float(gamma[c]) ), one rounding.
 // Memory order: tiles of 256 physical rows x 32 channels, [row tile][channel tile][row][32],
 // each tile 16 KiB and laid out exactly as the restoration kernel wants it in LDS (the four
@@ -27,7 +27,7 @@ __device__ __forceinline__ int logical_row(int p, int d_kv, int d_kv_pad, int hd
   const int grp = p >> 7;
   if (grp * kPairGroup >= d_kv) return -1;                // padding
   const int member = (p >> 5) & 1, i = p & 31;
-  const int u = 16 * ((i >> 2) & 1) + 4 * (i >> 3) + (i & 3);
+  const int u = 8 * ((i >> 2) & 3) + 4 * (i >> 4) + (i & 3);
   const int gph = hd >> 6;
   const int head = grp / gph, qq = grp - head * gph;
   const int pair = 32 * qq + u;
@@ -228,8 +228,8 @@ hipError_t launch_kv_rows(const KvRowsArgs& a, bool to_pool, hipStream_t stream)
 }
 
 // ---- matrix-pipe duty-cycle probe (measurement only) -----------------------------------------
-// Every CU runs bursts of v_mfma_f32_32x32x16_bf16 on register operands (eight waves, two per
-// SIMD, eight accumulator blocks each) gated by the constant-rate wall clock: busy while
+// Every CU runs bursts of v_mfma_f32_32x32x16_bf16 (or, for comparison, v_mfma_f32_16x16x32_bf16)
+// on register operands (eight waves, two per SIMD, 128 accumulator registers each) gated by the constant-rate wall clock: busy while
 // (t mod period) < busy, asleep otherwise; with `half_phase` odd workgroups are busy in the
 // other half of the period.  The matrix ops issued inside the busy windows are counted.
 // If the chip's power management averaged over time, a 50 % duty cycle would let the busy
@@ -240,6 +240,11 @@ typedef __attribute__((ext_vector_type(8))) __bf16 probe_bf16x8;
 typedef __attribute__((ext_vector_type(16))) float probe_f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t probe_u32x4;
 
+typedef __attribute__((ext_vector_type(4))) float probe_f32x4;
+
+// SHAPE 0: 32 ops 32x32x16 per batch (8 accumulator blocks of 16 registers);
+// SHAPE 1: 64 ops 16x16x32 per batch (16 accumulator blocks of 4 registers): the same flop.
+template <int SHAPE>
 __global__ __launch_bounds__(512) void mfma_duty_kernel(const probe_u32x4* __restrict__ ops,
                                                         float* __restrict__ sink,
                                                         unsigned long long period_ticks,
@@ -247,15 +252,20 @@ __global__ __launch_bounds__(512) void mfma_duty_kernel(const probe_u32x4* __res
                                                         unsigned long long total_ticks, int half_phase,
                                                         unsigned long long* __restrict__ batches_out) {
   probe_f32x16 acc[8];
+  probe_f32x4 acc4[16];
 #pragma unroll
   for (int i = 0; i < 8; ++i)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
-  probe_bf16x8 a[4], b[2];
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc4[i][v] = 0.f;
+  probe_bf16x8 a[4], b[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) a[i] = __builtin_bit_cast(probe_bf16x8, ops[(threadIdx.x * 8 + i) & 2047]);
 #pragma unroll
-  for (int i = 0; i < 2; ++i) b[i] = __builtin_bit_cast(probe_bf16x8, ops[(threadIdx.x * 8 + 4 + i) & 2047]);
+  for (int i = 0; i < 4; ++i) b[i] = __builtin_bit_cast(probe_bf16x8, ops[(threadIdx.x * 8 + 4 + i) & 2047]);
   const unsigned long long t_begin = wall_clock64();      // 100 MHz
   const unsigned long long phase = (half_phase && (blockIdx.x & 1)) ? period_ticks / 2 : 0;
   unsigned long long batches = 0;
@@ -263,12 +273,20 @@ __global__ __launch_bounds__(512) void mfma_duty_kernel(const probe_u32x4* __res
     const unsigned long long t = wall_clock64();
     if (t - t_begin >= total_ticks) break;
     if (((t + phase) % period_ticks) < busy_ticks) {
-      for (int it = 0; it < 4; ++it) {                    // one batch = 32 matrix ops per wave
+      for (int it = 0; it < 4; ++it) {                    // one batch = 32 * 32768 flop per wave
+        if constexpr (SHAPE == 0) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+          for (int i = 0; i < 4; ++i)
 #pragma unroll
-          for (int j = 0; j < 2; ++j)
-            acc[i * 2 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i * 2 + j], 0, 0, 0);
+            for (int j = 0; j < 2; ++j)
+              acc[i * 2 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i * 2 + j], 0, 0, 0);
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              acc4[i * 4 + j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc4[i * 4 + j], 0, 0, 0);
+        }
       }
       ++batches;
     } else {
@@ -280,12 +298,16 @@ __global__ __launch_bounds__(512) void mfma_duty_kernel(const probe_u32x4* __res
   for (int i = 0; i < 8; ++i)
 #pragma unroll
     for (int v = 0; v < 16; ++v) s += acc[i][v];
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) s += acc4[i][v];
   sink[blockIdx.x * blockDim.x + threadIdx.x] = s;
   if ((threadIdx.x & 63) == 0) batches_out[blockIdx.x * 8 + (threadIdx.x >> 6)] = batches;
 }
 
 hipError_t run_mfma_duty(double period_us, double duty, int half_phase, double total_us,
-                         int zero_operands, double* out_tflops) {
+                         int zero_operands, int op_shape, double* out_tflops) {
   const int n_wg = 256, n_waves = n_wg * 8;
   probe_u32x4* ops = nullptr;
   float* sink = nullptr;
@@ -310,8 +332,12 @@ hipError_t run_mfma_duty(double period_us, double duty, int half_phase, double t
     const unsigned long long B = (unsigned long long)(period_us * 100.0 * duty);
     const unsigned long long T = (unsigned long long)(total_us * 100.0);
     for (int rep = 0; rep < 2 && e == hipSuccess; ++rep) {   // the first run warms up
-      hipLaunchKernelGGL(mfma_duty_kernel, dim3(n_wg), dim3(512), 0, nullptr, ops, sink, P ? P : 1, B, T,
-                         half_phase, batches);
+      if (op_shape == 0)
+        hipLaunchKernelGGL(mfma_duty_kernel<0>, dim3(n_wg), dim3(512), 0, nullptr, ops, sink, P ? P : 1, B, T,
+                           half_phase, batches);
+      else
+        hipLaunchKernelGGL(mfma_duty_kernel<1>, dim3(n_wg), dim3(512), 0, nullptr, ops, sink, P ? P : 1, B, T,
+                           half_phase, batches);
       e = hipGetLastError();
       if (e == hipSuccess) e = hipDeviceSynchronize();
     }

@@ -29,7 +29,11 @@ constexpr int kWTileBytes = kTileF * kTileK * 2;   // one packed weight tile: 25
 // bank-conflict free).  Weight tiles have 64-byte rows (4 chunks): chunk c of row r sits at
 // position c ^ swz_w(r).  Activation super-tiles have 128-byte rows (8 chunks): chunk c of
 // row r sits at position c ^ swz_x(r).  The pack kernel bakes swz_w into the global layout.
-__host__ __device__ inline int swz_w(int row) { return (row >> 2) & 3; }
+// A fragment read takes 16 consecutive rows per lane quarter, quarter q reading chunk q (+ 4
+// for odd steps of the activations); both functions were checked with the bank-conflict
+// counter (0 conflicts) -- (row >> 2) & 3 for the weights gives two-way conflicts with this
+// access shape.
+__host__ __device__ inline int swz_w(int row) { return (row >> 1) & 3; }
 __host__ __device__ inline int swz_x(int row) { return (row >> 1) & 7; }
 
 inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
@@ -99,7 +103,7 @@ hipError_t configure_kernels();   // one-time function attributes (dynamic LDS s
 // the busy windows of a duty-cycled burst pattern; allocates and frees its own buffers and
 // synchronises the device.
 hipError_t run_mfma_duty(double period_us, double duty, int half_phase, double total_us,
-                         int zero_operands, double* out_tflops);
+                         int zero_operands, int op_shape, double* out_tflops);
 
 // One contiguous piece of a layer's hidden states in the host store and where it goes in
 // the HBM staging buffer.  `bytes` is a multiple of 16.
