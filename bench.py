@@ -30,8 +30,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16, vendor figure without s
 # profiles/restore_kernel_llama3-8b-gqa-T8192.md.  Bytes per layer (a launch over several layers
 # moves that many times as much); None where not profiled.
 TRAFFIC_BYTES_PER_LAUNCH = {"llama3-8b-gqa-T8192": 2.436e8}
-# the same per layer inside a launch over 8 layers (fetched 200.4 MiB + written 32.03 MiB)
-TRAFFIC_BYTES_PER_LAYER_FUSED = {"llama3-8b-gqa-T8192": 2.437e8}
+# the same per layer inside a launch over 8 layers (fetched 200.1 MiB + written 32.0 MiB)
+TRAFFIC_BYTES_PER_LAYER_FUSED = {"llama3-8b-gqa-T8192": 2.4335e8}
 
 
 def log(*a):
@@ -108,6 +108,10 @@ def main():
     ap.add_argument("--d-model", type=int, default=None,
                     help="diagnostic: override the workload's d_model (a multiple of 64) to separate the cost "
                          "per channel from the fixed cost per tile; implies a different synthetic shape")
+    ap.add_argument("--one-tile", action="store_true",
+                    help="diagnostic: shrink the workload to ONE workgroup tile (256 tokens, one KV head of 128 "
+                         "-> 256 fused features), one launch per layer: the kernel alone on an otherwise idle "
+                         "chip, at full clock; with two --d-model values it gives the loop's cycles per step")
     ap.add_argument("--vendor-gemm", action="store_true",
                     help="context: also time the vendor library's plain bf16 GEMM (torch.mm = hipBLASLt) on the "
                          "same hidden states and unpacked weights, layer after layer, no norm / RoPE / paging")
@@ -150,6 +154,11 @@ def main():
     if args.d_model:
         import dataclasses
         w = dataclasses.replace(w, d_model=args.d_model, name=f"{w.name}-d{args.d_model}")
+    if args.one_tile:
+        import dataclasses
+        w = dataclasses.replace(w, n_q_heads=1, n_kv_heads=1, head_dim=128, tokens=256, n_seq=1,
+                                name=f"{w.name}-one-tile")
+        args.layers_per_launch = 1
     ragged = w.n_seq != 1
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)

@@ -24,7 +24,8 @@ def hipcc_path():
 # writes libhcache_diag_<names>.so next to the library; HCACHE_LIB=<path> makes the binding
 # load it instead.
 DIAG = {"no_sumsq": "-DHC_DIAG_NO_SUMSQ", "no_loads": "-DHC_DIAG_NO_LOADS",
-        "no_ldsread": "-DHC_DIAG_NO_LDSREAD", "no_barrier": "-DHC_DIAG_NO_BARRIER"}
+        "no_ldsread": "-DHC_DIAG_NO_LDSREAD", "no_barrier": "-DHC_DIAG_NO_BARRIER",
+        "no_epilogue": "-DHC_DIAG_NO_EPILOGUE"}
 
 
 def build(verbose=False, extra_flags=(), out=None, tag=""):
