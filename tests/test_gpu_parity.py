@@ -87,6 +87,12 @@ SHAPES = [
     (64, 1, 64, 70, 0),        # fewer d_model steps (2) than the weight ring is deep (4)
     (128, 2, 64, 300, 1),      # 4 steps: the ring is filled exactly once
     (192, 1, 64, 33, 0),
+    # head dimensions other than 64 and 128: a tile's two pair groups are half a head (256) or
+    # straddle heads (192), which the epilogue's write-out order has to follow
+    (1024, 2, 256, 300, 0),
+    (512, 2, 256, 100, 1),
+    (1024, 2, 192, 280, 0),    # d_kv = 384: three pair groups per head, padded to 512 rows
+    (512, 1, 192, 131, 1),
 ]
 
 
