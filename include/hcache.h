@@ -392,8 +392,8 @@ hc_status hc_timing_end_stats(hc_ctx* ctx, void* stream, double* out_avg_ms, dou
  * total_us; with half_phase != 0 every other workgroup is busy in the other half of the period
  * (so half the chip is idle at any moment).  *out_tflops = matrix-op rate inside the busy
  * windows, scaled to the whole chip.  zero_operands != 0 uses all-zero operands (no operand
- * toggling).  op_shape selects the matrix op: 0 = 32x32x16 (the restoration kernel's), 1 =
- * 16x16x32 (same flop per burst).  Allocates and frees small device buffers, synchronises the
+ * toggling).  op_shape selects the matrix op: 0 = 32x32x16, 1 = 16x16x32 (the
+ * restoration kernel's; same flop per burst).  Allocates and frees small device buffers, synchronises the
  * device. */
 hc_status hc_diag_mfma_duty(double period_us, double duty, int32_t half_phase, double total_us,
                             int32_t zero_operands, int32_t op_shape, double* out_tflops);

@@ -228,7 +228,7 @@ hipError_t launch_kv_rows(const KvRowsArgs& a, bool to_pool, hipStream_t stream)
 }
 
 // ---- matrix-pipe duty-cycle probe (measurement only) -----------------------------------------
-// Every CU runs bursts of v_mfma_f32_32x32x16_bf16 (or, for comparison, v_mfma_f32_16x16x32_bf16)
+// Every CU runs bursts of v_mfma_f32_32x32x16_bf16 or v_mfma_f32_16x16x32_bf16 (the restoration kernel's op)
 // on register operands (eight waves, two per SIMD, 128 accumulator registers each) gated by the constant-rate wall clock: busy while
 // (t mod period) < busy, asleep otherwise; with `half_phase` odd workgroups are busy in the
 // other half of the period.  The matrix ops issued inside the busy windows are counted.
