@@ -25,6 +25,8 @@ hipError_t launch_restore(const RestoreArgs& a, LayerBatch* batch, int n_layers,
   g.nt = (a.n_tok + kTileT - 1) / kTileT;
   // Super-tile shape: fewest rounds on the busiest XCD (an XCD runs 32 workgroups at a
   // time, one per CU), then the most row sharing (smallest 1/GF + 1/GT), then fewest slots.
+  // Of two shapes that tie (GF x GT = 4 x 8 and 8 x 4 for 8 x 32 tiles) the one with fewer
+  // feature tiles is met first and kept: it measured 105.4 against 107.0 us per layer.
   int best_rounds = 1 << 30, best_slots = 1 << 30, best_share = 1 << 30;
   g.gf_shift = g.g_shift = 0;
   for (int fs = 0; fs <= 5; ++fs) {
