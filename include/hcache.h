@@ -386,6 +386,16 @@ hc_status hc_timing_end(hc_ctx* ctx, void* stream, double* out_avg_ms, int32_t* 
 hc_status hc_timing_end_stats(hc_ctx* ctx, void* stream, double* out_avg_ms, double* out_min_ms,
                               double* out_median_ms, int32_t* out_launches);
 
+/* Host-side view of the restoration kernel's launch shape (no device work; for tests and
+ * profiles).  For a layer of d_kv x n_tok and a launch over n_layers (1..8) layers:
+ * out_shape[6] = { feature tiles, token tiles, super-tile width in feature tiles, in token
+ * tiles, workgroup slots per layer, 0 }.  When out_tiles is not NULL it receives, for every
+ * layer and slot in launch order, the pair (feature tile, token tile) the slot's workgroup
+ * works on, or (-1, -1) for a padding slot; out_capacity is its size in pairs (HC_ERANGE when
+ * too small).  Workgroup w of a launch runs on XCD w % 8. */
+hc_status hc_diag_tile_map(int32_t d_kv, int32_t n_tok, int32_t n_layers, int32_t* out_shape,
+                           int32_t* out_tiles, int64_t out_capacity);
+
 /* Matrix-pipe duty-cycle probe (measurement only; evidence for how the chip's power management
  * bounds the restoration kernel).  All compute units run bursts of bf16 matrix ops on register
  * operands, busy while (wall clock mod period_us) < duty * period_us and asleep otherwise, for

@@ -87,6 +87,7 @@ def _load():
         "hc_saver_fence": (i32, [vp, vp]),
         "hc_saver_save_layer_host": (i32, [vp, i32, vp, i32, vp]),
         "hc_saver_flush": (i32, [vp]),
+        "hc_diag_tile_map": (i32, [i32, i32, i32, p(i32), p(i32), C.c_int64]),
         "hc_diag_mfma_duty": (i32, [C.c_double, C.c_double, i32, C.c_double, i32, i32, p(C.c_double)]),
         "hc_timing_begin": (i32, [vp]),
         "hc_timing_end": (i32, [vp, vp, p(C.c_double), p(i32)]),
@@ -107,7 +108,7 @@ EXPORTED = ("hc_last_error hc_version hc_validate_desc hc_create hc_destroy hc_s
             "hc_saver_flush hc_partition_layers hc_gather_kv hc_scatter_kv "
             "hc_restore_context_mixed hc_set_layer_weights_affine hc_saver_save_layer_deferred "
             "hc_saver_fence hc_restore_kv_layers hc_restore_contexts hc_timing_end_stats "
-            "hc_restore_context_static hc_static_stage_bytes hc_poison_staging hc_diag_mfma_duty").split()
+            "hc_restore_context_static hc_static_stage_bytes hc_poison_staging hc_diag_mfma_duty hc_diag_tile_map").split()
 
 
 def _check(status):
@@ -117,6 +118,18 @@ def _check(status):
 
 def static_stage_bytes():
     return lib.hc_static_stage_bytes()
+
+
+def diag_tile_map(d_kv, n_tok, n_layers=1):
+    """(shape dict, tiles int32 [n_layers, slots, 2]) of a restoration launch; host only."""
+    import numpy as np
+    shape = (C.c_int32 * 6)()
+    _check(lib.hc_diag_tile_map(d_kv, n_tok, n_layers, shape, None, 0))
+    slots = shape[4]
+    tiles = np.empty((n_layers, slots, 2), dtype=np.int32)
+    _check(lib.hc_diag_tile_map(d_kv, n_tok, n_layers, shape,
+                                tiles.ctypes.data_as(C.POINTER(C.c_int32)), n_layers * slots))
+    return {"nf": shape[0], "nt": shape[1], "gf": shape[2], "gt": shape[3], "slots": slots}, tiles
 
 
 def diag_mfma_duty(period_us, duty, half_phase=False, total_us=60000.0, zero_operands=False, op_shape=0):

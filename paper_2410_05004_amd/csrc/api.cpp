@@ -448,6 +448,34 @@ hc_status hc_set_loader(hc_ctx* ctx, int32_t mode) {
   return HC_OK;
 }
 
+hc_status hc_diag_tile_map(int32_t d_kv, int32_t n_tok, int32_t n_layers, int32_t* out_shape,
+                           int32_t* out_tiles, int64_t out_capacity) {
+  clear_error();
+  if (!out_shape) return fail(HC_EINVAL, "null output pointer");
+  if (d_kv <= 0 || n_tok <= 0 || n_layers <= 0 || n_layers > kMaxLayersPerLaunch)
+    return fail(HC_EINVAL, "d_kv > 0, n_tok > 0, 1 <= n_layers <= 8");
+  TileGrid g;
+  const int slots = choose_tile_grid(2 * round_up(d_kv, kPartAlign) / kTileF, (n_tok + kTileT - 1) / kTileT, g);
+  out_shape[0] = g.nf;
+  out_shape[1] = g.nt;
+  out_shape[2] = 1 << g.gf_shift;
+  out_shape[3] = 1 << (g.g_shift - g.gf_shift);
+  out_shape[4] = slots;
+  out_shape[5] = 0;
+  if (!out_tiles) return HC_OK;
+  if (out_capacity < (int64_t)n_layers * slots) return fail(HC_ERANGE, "out_tiles too small");
+  for (int l = 0; l < n_layers; ++l)
+    for (int wg = 0; wg < slots; ++wg) {
+      int tf, tt;
+      // a launch over one layer passes no rotation, a launch over several the layer's index
+      const bool ok = slot_to_tile(g, wg, n_layers > 1 ? l : 0, tf, tt);
+      int32_t* o = out_tiles + ((int64_t)l * slots + wg) * 2;
+      o[0] = ok ? tf : -1;
+      o[1] = ok ? tt : -1;
+    }
+  return HC_OK;
+}
+
 hc_status hc_diag_mfma_duty(double period_us, double duty, int32_t half_phase, double total_us,
                             int32_t zero_operands, int32_t op_shape, double* out_tflops) {
   clear_error();

@@ -267,3 +267,39 @@ def test_store_index_is_safe_across_threads(hc):
         t.join()
     assert not errors, errors
     st.destroy()
+
+
+def test_tile_map_covers_every_tile_once_and_balances_the_xcds(hc):
+    """The kernel's slot -> tile map (the same function the kernel compiles, evaluated on the
+    host): for a range of layer shapes and launch depths every tile of every layer belongs to
+    exactly one slot, a slot's workgroup stays inside its XCD's super tiles (slot % 8), and over
+    an eight-layer launch the XCDs differ by at most one super tile's worth of tiles."""
+    import numpy as np
+    shapes = [(1024, 8192), (4096, 2048), (7168, 2048), (5120, 1536), (5120, 1600), (192, 257),
+              (128, 1), (640, 600), (1024, 32768), (384, 280)]
+    for d_kv, n_tok in shapes:
+        for n_layers in (1, 3, 8):
+            shape, tiles = hc.diag_tile_map(d_kv, n_tok, n_layers)
+            nf, nt, slots = shape["nf"], shape["nt"], shape["slots"]
+            assert slots % 8 == 0 and shape["gf"] * shape["gt"] <= 32
+            assert nf == 2 * (-(-d_kv // 128) * 128) // 256 and nt == -(-n_tok // 256)
+            per_xcd = np.zeros(8, dtype=np.int64)
+            for l in range(n_layers):
+                t = tiles[l]
+                real = t[:, 0] >= 0
+                assert ((t[real, 0] < nf) & (t[real, 1] < nt)).all()
+                flat = t[real, 0].astype(np.int64) * nt + t[real, 1]
+                assert flat.size == nf * nt and np.unique(flat).size == nf * nt, (d_kv, n_tok, n_layers, l)
+                # workgroup l * slots + w runs on XCD (l * slots + w) % 8 = w % 8
+                per_xcd += np.bincount(np.nonzero(real)[0] % 8, minlength=8)
+                # the tiles an XCD works on in one layer come from whole super tiles
+                for x in range(8):
+                    tx = t[real & (np.arange(slots) % 8 == x)]
+                    supers = {(int(a) // shape["gf"], int(b) // shape["gt"]) for a, b in tx}
+                    assert len(tx) <= len(supers) * shape["gf"] * shape["gt"]
+            if n_layers == 8:
+                assert per_xcd.max() - per_xcd.min() <= shape["gf"] * shape["gt"], (d_kv, n_tok, per_xcd)
+    # a single-layer launch applies no rotation: slot w of layer 0 is the same in both
+    one = hc.diag_tile_map(7168, 2048, 1)[1]
+    many = hc.diag_tile_map(7168, 2048, 8)[1]
+    assert (one[0] == many[0]).all() and not (many[1] == many[0]).all()
