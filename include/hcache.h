@@ -374,6 +374,27 @@ hc_status hc_partition_layers(int32_t n_layers, double io_h, double io_kv, doubl
  * waves share compute units with the restoration kernel and slow it down). */
 hc_status hc_set_loader(hc_ctx* ctx, int32_t mode);
 
+/* Split launches (paper Section 4.1.1, "Performance considerations": how well the projection
+ * uses the device depends on the token count).  The restoration kernel of a single layer
+ * (hc_restore_kv, hc_restore_kv_ragged, hc_restore_context*, hc_restore_contexts) runs one
+ * 256-feature x 256-token tile per workgroup and compute unit, in rounds of 256, and a last
+ * round with few tiles takes as long as a full one.  mode 1 (default): when a cost model says it
+ * pays (a last round at most half full, d_model of about 2048 or more), the token tiles outside
+ * the full rounds are computed by several workgroups each, every one over a contiguous share
+ * of d_model, into an fp32 workspace the context owns (allocated by hc_create, 66 MiB), and a
+ * second launch adds the shares up in a fixed order and finishes them (normalisation, RoPE,
+ * scatter).  Results are deterministic and within the same tolerance, but not bit-identical to
+ * an unsplit launch (fp32 summation order).  Split launches of one context are ordered after
+ * each other through an event, whatever their streams.  mode 0: never split.  mode 2: split
+ * whenever the shape allows it (tests and measurements).  Launches over several layers
+ * (hc_restore_kv_layers) never split. */
+hc_status hc_set_split(hc_ctx* ctx, int32_t mode);
+/* Host-side view of that decision for a layer of d_model, d_kv and n_tok under `mode` (no
+ * device work): out_plan[8] = { 1 if split else 0, feature tiles, token tiles, token tiles
+ * computed whole, tiles that are split, workgroups per split tile, workgroup slots of the whole
+ * tiles (first in the grid; padding slots included), workgroups of the finishing launch }. */
+hc_status hc_diag_split_plan(int32_t d_model, int32_t d_kv, int32_t n_tok, int32_t mode, int32_t* out_plan);
+
 /* ---- measurement hooks -------------------------------------------------------------
  * Average duration in milliseconds of the restoration kernel launches (one per layer, or
  * one per group of layers under hc_restore_kv_layers) queued on

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     static_stage_bytes,
     diag_mfma_duty,
     diag_tile_map,
+    diag_split_plan,
     partition_layers,
     HC_OK, HC_EINVAL, HC_ERANGE, HC_EALIGN, HC_ENOMEM, HC_EHIP, HC_ESTATE,
     HC_DEV_BAD_POSITION, HC_DEV_BAD_PAGE, HC_NORM_RMS, HC_NORM_LAYER,

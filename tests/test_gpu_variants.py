@@ -38,7 +38,8 @@ VARIANTS = [
 @pytest.mark.parametrize("norm_kind,rope_style,shift,with_bias", VARIANTS)
 def test_variant_matches_oracle(hc, norm_kind, rope_style, shift, with_bias):
     """Every element of a 3-tile x 3-tile problem with ragged tails (d_kv = 640 pads the K and
-    V parts), rows with a clearly non-zero mean, unsorted positions."""
+    V parts), rows with a clearly non-zero mean, unsorted positions; once with each of the 15
+    tiles' d_model loops split in two and finished by a second launch, once unsplit."""
     rng = np.random.default_rng([5, norm_kind, rope_style, shift, with_bias])
     d_model, n_kv, hd, B, T = 1024, 5, 128, 16, 600
     d_kv = n_kv * hd
@@ -54,25 +55,28 @@ def test_variant_matches_oracle(hc, norm_kind, rope_style, shift, with_bias):
     pos = rng.permutation(n_blocks * B)[:T].astype(np.int32)
     num_pages = n_blocks + 9
     bt = rng.permutation(num_pages)[:n_blocks].astype(np.int32)
+    assert hc.diag_split_plan(d_model, d_kv, T, 2)["n_split"] == 2
     ctx = hc.Context(desc)
     s = gh.stream_handle()
-    pool = gh.new_pool(num_pages, B, n_kv, hd)
-    ctx.set_kv_pool(0, pool, num_pages)
     dev = [gh.to_dev_bf16(a) if a is not None else None for a in (wkv, gamma, beta, bias)]
     if shift or with_bias or norm_kind == 1:
         ctx.set_layer_weights_affine(0, dev[0], dev[1], dev[2], dev[3], s)
     else:
         ctx.set_layer_weights(0, dev[0], dev[1], s)
-    ctx.restore_kv(0, gh.to_dev_bf16(x), gh.to_dev_i32(pos), T, gh.to_dev_i32(bt), n_blocks, s)
-    assert ctx.poll_device_error(s) == 0
     ora = np.full((num_pages, 2, B, n_kv, hd), np.nan)
     f = syn.bf16_bits_to_f64
     oracle.restore_kv(ora, f(x), f(gamma), f(wkv), pos, bt,
                       beta=None if beta is None else f(beta), bias=None if bias is None else f(bias),
                       **gh.oracle_kw(desc))
-    worst = gh.compare_pool(gh.pool_bits(pool), ora)
-    print(f"variant norm={norm_kind} rope={rope_style} shift={shift} bias={with_bias}: "
-          f"worst error {worst * gh.TOL:.4f} x RMS", flush=True)
+    for split in (2, 0):
+        ctx.set_split(split)
+        pool = gh.new_pool(num_pages, B, n_kv, hd)
+        ctx.set_kv_pool(0, pool, num_pages)
+        ctx.restore_kv(0, gh.to_dev_bf16(x), gh.to_dev_i32(pos), T, gh.to_dev_i32(bt), n_blocks, s)
+        assert ctx.poll_device_error(s) == 0
+        worst = gh.compare_pool(gh.pool_bits(pool), ora)
+        print(f"variant norm={norm_kind} rope={rope_style} shift={shift} bias={with_bias} split={split}: "
+              f"worst error {worst * gh.TOL:.4f} x RMS", flush=True)
     ctx.destroy()
 
 

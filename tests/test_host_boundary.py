@@ -303,3 +303,50 @@ def test_tile_map_covers_every_tile_once_and_balances_the_xcds(hc):
     one = hc.diag_tile_map(7168, 2048, 1)[1]
     many = hc.diag_tile_map(7168, 2048, 8)[1]
     assert (one[0] == many[0]).all() and not (many[1] == many[0]).all()
+
+
+def test_split_plan_invariants(hc):
+    """hc_diag_split_plan (host logic only).  Whenever a launch is split: its last round of 256
+    workgroups would be at most half full; the whole tiles are the whole rows of token tiles
+    that fit the full rounds and their slot grid is the one an unsplit launch of that many
+    tokens gets; every share of a split loop is at least 8 x 64 channels; the workspace holds
+    one slot per split workgroup (256 at most).  Mode 1 splits a subset of what mode 2 splits,
+    in the same way, and only where its cost model (1.5 x the 64-channel steps of a whole tile against
+    steps / ways + 0.143 x tiles x ways + 15) says so; mode 0 never splits."""
+    for d_model in (256, 1024, 2048, 4096, 5120, 7168, 8192):
+        nm = d_model // 64
+        for d_kv in (64, 640, 1024, 5120, 7168):
+            for n_tok in list(range(1, 4500, 173)) + [256, 1536, 1600, 2048, 8192, 16384]:
+                p0, p1, p = (hc.diag_split_plan(d_model, d_kv, n_tok, m) for m in (0, 1, 2))
+                nf, nt = p["nf"], p["nt"]
+                assert nf == 2 * (-(-d_kv // 128) * 128) // 256 and nt == -(-n_tok // 256)
+                unsplit = dict(p, split=0, nt_main=nt, n_tail=0, n_split=1, main_slots=0, fixup_workgroups=0)
+                assert p0 == unsplit and p1 in (unsplit, p)
+                if not p["split"]:
+                    assert p == unsplit
+                    continue
+                rem = nf * nt % 256
+                assert 0 < rem <= 128
+                assert nf * p["nt_main"] <= nf * nt - rem                   # whole tiles stay within the full rounds
+                assert nf * (p["nt_main"] + 1) > nf * nt - rem              # ... and no further row would
+                assert p["n_tail"] == nf * (nt - p["nt_main"]) > 0
+                assert 2 <= p["n_split"] <= 16 and p["n_tail"] * p["n_split"] <= 256
+                assert nm // p["n_split"] >= 8
+                assert p["fixup_workgroups"] == 4 * p["n_tail"]
+                if p["nt_main"]:
+                    assert p["main_slots"] == hc.diag_tile_map(d_kv, 256 * p["nt_main"], 1)[0]["slots"]
+                else:
+                    assert p["main_slots"] == 0
+                cost = nm / p["n_split"] + 0.143 * p["n_tail"] * p["n_split"] + 15
+                if abs(cost - 1.5 * nm) > 1e-3:
+                    assert p1["split"] == (cost < 1.5 * nm), (d_model, d_kv, n_tok, cost)
+    p = hc.diag_split_plan(5120, 5120, 1600)                                # 40 x 7 tiles
+    assert (p["split"], p["nt_main"], p["n_tail"], p["n_split"], p["main_slots"]) == (1, 6, 40, 4, 256)
+    assert hc.diag_split_plan(4096, 1024, 8192, 2)["split"] == 0            # 8 x 32 tiles: exactly one round
+    assert hc.diag_split_plan(5120, 5120, 1536, 2)["split"] == 0            # 240 of 256: full enough
+    assert hc.diag_split_plan(1024, 640, 600)["split"] == 0                 # narrow model: does not pay
+    assert hc.diag_split_plan(1024, 640, 600, 2)["n_split"] == 2
+    with pytest.raises(hc.HCacheError):
+        hc.diag_split_plan(100, 64, 10)
+    with pytest.raises(hc.HCacheError):
+        hc.diag_split_plan(1024, 64, 10, 3)
