@@ -175,39 +175,50 @@ def test_single_context_workloads(hc, index):
     ctx.destroy()
 
 
-SPLIT_CASE = dict(d_model=1024, n_kv=16, hd=128, T=4315, B=16, offset=1000)
+SPLIT_CASES = {
+    # 16 feature tiles x 17 token tiles: the first 16 rows of token tiles fill one round of 256
+    # workgroups and are computed whole, the 16 tiles of the ragged 17th are split in two
+    "16x17": dict(d_model=1024, n_kv=16, hd=128, T=4315, B=16, offset=1000, seed=20,
+                  plan=dict(nt_main=16, n_tail=16, n_split=2, main_slots=256)),
+    # 5 x 52 = 260 tiles (d_kv = 640 pads the K and V parts): 51 whole rows (255 tiles in 256
+    # slots), the five tiles of the ragged last row split in two
+    "5x52": dict(d_model=1024, n_kv=5, hd=128, T=13156, B=16, offset=1000, seed=20,
+                 plan=dict(nt_main=51, n_tail=5, n_split=2, main_slots=256)),
+}
 
 
-def split_case_inputs(seed=20):
-    """Seeded inputs of the split-launch test below and the token rows it checks element by
-    element (also read by the CPU feasibility test).  The seed is one for which the prescribed
+def split_case_inputs(name):
+    """Seeded inputs of a split-launch test below and the token rows it checks element by
+    element (also read by the CPU feasibility test).  The seeds are ones for which the prescribed
     bf16 arithmetic itself stays inside the tolerance on those rows
-    (tests/test_tolerance_model.py; seeds 17-19 sit at 2.04e-2 - 2.15e-2 x RMS_head)."""
-    c = SPLIT_CASE
+    (tests/test_tolerance_model.py; for the first case seeds 17-19 sit at 2.04e-2 - 2.15e-2 x
+    RMS_head)."""
+    c = SPLIT_CASES[name]
     T, B = c["T"], c["B"]
-    rng = np.random.default_rng([seed, c["d_model"], T])
+    rng = np.random.default_rng([c["seed"], c["d_model"], T])
     case = gh.LayerCase(rng, c["d_model"], c["n_kv"], c["hd"], T)
     n_blocks = (c["offset"] + T + B - 1) // B
     num_pages = n_blocks + 5
     bt = rng.permutation(num_pages)[:n_blocks].astype(np.int32)
     pos = (c["offset"] + rng.permutation(T)).astype(np.int32)
-    rows = np.union1d(np.arange(4096, T), sample_rows(rng, T, range(256, T, 256), range(0, 8), [], n_random=600))
+    last_row = (T - 1) // 256 * 256
+    rows = np.union1d(np.arange(last_row, T), sample_rows(rng, T, range(256, T, 256), range(0, 8), [], n_random=600))
     return case, pos, bt, num_pages, rows
 
 
-def test_split_launch_whole_and_split_tiles(hc):
-    """16 feature tiles x 17 token tiles (d_model 1024, d_kv 2048, 4315 tokens in scrambled
-    order): the first 16 token tiles fill one round of 256 workgroups and are computed whole,
-    the 16 tiles of the ragged 17th have their d_model loop split in two and are finished by a
-    second launch.  Exact written set, the random projection over every token, and every
-    element of all 219 tokens of the split tiles plus ~650 sampled tokens of the whole ones;
-    then the same with splitting switched off."""
+@pytest.mark.parametrize("name", list(SPLIT_CASES))
+def test_split_launch_whole_and_split_tiles(hc, name):
+    """Launches of more than 256 tiles whose last few tiles have their d_model loop split: whole
+    tiles and split workgroups in one grid, then the finishing launch; tokens in scrambled
+    order.  Exact written set, the random projection over every token, and every element of
+    all tokens of the last, ragged row of token tiles (where the split tiles are) plus ~650
+    sampled tokens of the whole rows; then the same with splitting switched off."""
     import torch
-    c = SPLIT_CASE
+    c = SPLIT_CASES[name]
     d_model, n_kv, hd, T, B = c["d_model"], c["n_kv"], c["hd"], c["T"], c["B"]
     plan = hc.diag_split_plan(d_model, n_kv * hd, T, 2)
-    assert (plan["split"], plan["nt_main"], plan["n_tail"], plan["n_split"], plan["main_slots"]) == (1, 16, 16, 2, 256)
-    case, pos, bt, num_pages, rows = split_case_inputs()
+    assert plan["split"] == 1 and {k: plan[k] for k in c["plan"]} == c["plan"], plan
+    case, pos, bt, num_pages, rows = split_case_inputs(name)
     desc = gh.make_desc(hc, n_layers=1, d_model=d_model, n_q_heads=n_kv, n_kv_heads=n_kv, head_dim=hd,
                         block_size=B, max_position=c["offset"] + T, rope_theta=500000.0)
     ctx = hc.Context(desc)
@@ -224,7 +235,7 @@ def test_split_launch_whole_and_split_tiles(hc):
         torch.cuda.synchronize()
         res = check_layer(None, desc, gh.pool_bits(pool), case.x_bits, case.wkv_bits, case.gamma_bits, pos,
                           np.zeros(T, dtype=np.int64), bt[None, :], rows, np.random.default_rng(5))
-        print(f"split={split}: sampled worst {res[0]:.3e} x RMS_head; projection check "
+        print(f"{name} split={split}: sampled worst {res[0]:.3e} x RMS_head; projection check "
               f"K {res[1]:.3f} V {res[2]:.3f} of limit", flush=True)
     ctx.destroy()
 

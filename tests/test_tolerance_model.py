@@ -98,8 +98,8 @@ def test_inputs_of_the_split_launch_tests_are_feasible():
         r = feasible(case.x, case.gamma, case.wkv, pos, n_kv, hd, theta=500000.0, style=style)
         print(f"split shape {d_model}/{n_kv}/{hd}/{n_tok}/{style}: model error {r:.4f} x RMS_head")
         assert r <= TOL
-    case, pos, bt, num_pages, rows = tf.split_case_inputs()
-    c = tf.SPLIT_CASE
-    r = feasible(case.x[rows], case.gamma, case.wkv, pos[rows], c["n_kv"], c["hd"], theta=500000.0)
-    print(f"whole + split tiles, {len(rows)} rows checked element by element: model error {r:.4f} x RMS_head")
-    assert r <= MARGIN * TOL
+    for name, c in tf.SPLIT_CASES.items():
+        case, pos, bt, num_pages, rows = tf.split_case_inputs(name)
+        r = feasible(case.x[rows], case.gamma, case.wkv, pos[rows], c["n_kv"], c["hd"], theta=500000.0)
+        print(f"whole + split tiles {name}, {len(rows)} rows checked element by element: model error {r:.4f} x RMS_head")
+        assert r <= MARGIN * TOL
