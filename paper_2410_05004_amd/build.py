@@ -26,7 +26,7 @@ def hipcc_path():
 DIAG = {"no_sumsq": "-DHC_DIAG_NO_SUMSQ", "no_loads": "-DHC_DIAG_NO_LOADS",
         "no_ldsread": "-DHC_DIAG_NO_LDSREAD", "no_barrier": "-DHC_DIAG_NO_BARRIER",
         "no_epilogue": "-DHC_DIAG_NO_EPILOGUE", "no_rope_reads": "-DHC_DIAG_NO_ROPE_READS",
-        "few_stores": "-DHC_DIAG_FEW_STORES"}
+        "few_stores": "-DHC_DIAG_FEW_STORES", "same_tile": "-DHC_DIAG_SAME_TILE"}
 
 
 def build(verbose=False, extra_flags=(), out=None, tag=""):
