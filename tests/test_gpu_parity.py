@@ -205,6 +205,57 @@ def test_ragged_batch(hc, torch):
     ctx.destroy()
 
 
+def test_ragged_batch_split_launch_with_bad_rows(hc, torch):
+    """The ragged batch at d_model 2048 with the d_model loops split four ways (mode 2), so that
+    the per-token lookups (context by row offset, page by block table) run in the workgroups of
+    the finishing launch; one context's table has an unmapped block and one position lies past
+    the table: those rows are skipped and flagged, the rest matches the oracle.  Then unsplit."""
+    rng = np.random.default_rng(29)
+    d_model, n_kv, hd, B = 2048, 2, 128, 16
+    lens = np.array([37, 260, 1, 129, 300], dtype=np.int32)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T = int(cu[-1])
+    assert hc.diag_split_plan(d_model, n_kv * hd, T, 2)["n_split"] == 4
+    case = gh.LayerCase(rng, d_model, n_kv, hd, T)
+    pos = np.concatenate([rng.permutation(n) for n in lens]).astype(np.int32)
+    nblk = (lens + B - 1) // B
+    num_pages = int(nblk.sum()) + 9
+    perm = rng.permutation(num_pages).astype(np.int32)
+    tables = np.full((len(lens), int(nblk.max())), -1, dtype=np.int32)
+    at = 0
+    for i, n in enumerate(nblk):
+        tables[i, :n] = perm[at:at + n]
+        at += n
+    tables[1, 3] = -1                                 # context 1: positions 48..63 unmapped
+    pos[cu[4] + 7] = 400                              # context 4: block 25 is past its table
+    desc = gh.make_desc(hc, n_layers=1, d_model=d_model, n_q_heads=n_kv, n_kv_heads=n_kv,
+                        head_dim=hd, block_size=B, max_position=512)
+    good = np.ones(T, dtype=bool)
+    for i in range(len(lens)):
+        for t in range(cu[i], cu[i + 1]):
+            blk = pos[t] // B
+            good[t] = blk < tables.shape[1] and tables[i, blk] >= 0
+    assert (~good).sum() == 17
+    ora = np.full((num_pages, 2, B, n_kv, hd), np.nan)
+    seq_of = np.repeat(np.arange(len(lens)), lens)
+    keep = np.nonzero(good)[0]
+    cu_good = np.concatenate([[0], np.cumsum([good[cu[i]:cu[i + 1]].sum() for i in range(len(lens))])]).astype(np.int32)
+    oracle.restore_kv_ragged(ora, case.x[keep], case.gamma, case.wkv, pos[keep], cu_good, tables, **gh.oracle_kw(desc))
+    ctx = hc.Context(desc)
+    s = gh.stream_handle()
+    d_w, d_g, d_x = gh.to_dev_bf16(case.wkv_bits), gh.to_dev_bf16(case.gamma_bits), gh.to_dev_bf16(case.x_bits)
+    ctx.set_layer_weights(0, d_w, d_g, s)
+    d_pos, d_cu, d_tab = gh.to_dev_i32(pos), gh.to_dev_i32(cu), gh.to_dev_i32(tables)
+    for split in (2, 0):
+        ctx.set_split(split)
+        pool = gh.new_pool(num_pages, B, n_kv, hd)
+        ctx.set_kv_pool(0, pool, num_pages)
+        ctx.restore_kv_ragged(0, d_x, d_pos, T, d_cu, len(lens), d_tab, tables.shape[1], s)
+        assert ctx.poll_device_error(s) == (hc.HC_DEV_BAD_POSITION | hc.HC_DEV_BAD_PAGE)
+        gh.compare_pool(gh.pool_bits(pool), ora)
+    ctx.destroy()
+
+
 def test_bad_rows_are_skipped_and_flagged(hc, torch):
     rng = np.random.default_rng(23)
     d_model, n_kv, hd, B, T = 256, 1, 64, 16, 40
