@@ -108,6 +108,9 @@ def main():
     ap.add_argument("--d-model", type=int, default=None,
                     help="diagnostic: override the workload's d_model (a multiple of 64) to separate the cost "
                          "per channel from the fixed cost per tile; implies a different synthetic shape")
+    ap.add_argument("--tokens", type=int, default=None,
+                    help="diagnostic: override the workload's token count (single-context workloads): short "
+                         "contexts, where a layer fills only part of the chip")
     ap.add_argument("--one-tile", action="store_true",
                     help="diagnostic: shrink the workload to ONE workgroup tile (256 tokens, one KV head of 128 "
                          "-> 256 fused features), one launch per layer: the kernel alone on an otherwise idle "
@@ -154,6 +157,9 @@ def main():
     if args.d_model:
         import dataclasses
         w = dataclasses.replace(w, d_model=args.d_model, name=f"{w.name}-d{args.d_model}")
+    if args.tokens:
+        import dataclasses
+        w = dataclasses.replace(w, tokens=args.tokens, name=f"{w.name}-tokens{args.tokens}")
     if args.one_tile:
         import dataclasses
         w = dataclasses.replace(w, n_q_heads=1, n_kv_heads=1, head_dim=128, tokens=256, n_seq=1,

@@ -146,8 +146,10 @@ hc_status hc_restore_kv(hc_ctx* ctx, int32_t layer, const void* d_hidden,
 /* The same for layers [layer_begin, layer_begin + n_layers) of one context whose saved inputs
  * are ALL resident in HBM: h_d_hidden is a HOST array of n_layers device pointers, entry i =
  * bf16 [n_tok, d_model] of layer layer_begin + i; positions and block table are shared (one
- * context).  The layers go out in launches of up to 8 layers each, which
- * removes the gaps between per-layer kernels and lets the compute units run out of step.
+ * context).  The layers go out in launches of up to 8 layers each (for short contexts, whose
+ * layers have fewer than 32 tiles of 256 features x 256 tokens: as many layers as fill the 256
+ * compute units once, up to 32), which removes the gaps between per-layer kernels and lets the
+ * compute units run out of step.
  * Per layer the result is identical to hc_restore_kv's.  Every layer needs weights and a
  * pool (HC_ESTATE).  The pointer array is read during the call only. */
 hc_status hc_restore_kv_layers(hc_ctx* ctx, int32_t layer_begin, int32_t n_layers,
@@ -408,7 +410,7 @@ hc_status hc_timing_end_stats(hc_ctx* ctx, void* stream, double* out_avg_ms, dou
                               double* out_median_ms, int32_t* out_launches);
 
 /* Host-side view of the restoration kernel's launch shape (no device work; for tests and
- * profiles).  For a layer of d_kv x n_tok and a launch over n_layers (1..8) layers:
+ * profiles).  For a layer of d_kv x n_tok and a launch over n_layers (1..32) layers:
  * out_shape[6] = { feature tiles, token tiles, super-tile width in feature tiles, in token
  * tiles, workgroup slots per layer, 0 }.  When out_tiles is not NULL it receives, for every
  * layer and slot in launch order, the pair (feature tile, token tile) the slot's workgroup

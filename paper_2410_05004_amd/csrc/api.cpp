@@ -143,13 +143,14 @@ hc_status restore_layers(hc_ctx* ctx, int32_t layer_begin, int32_t n_layers,
     if (!aligned16(d_hidden[i])) return fail(HC_EALIGN, "hidden not 16-byte aligned");
   }
   RestoreArgs a = shared_args(ctx, d_positions, pos_base, n_tok, nullptr, 1, d_block_table, n_blocks);
+  const int per_launch = layers_per_launch(2 * ctx->d_kv_pad / kTileF, (n_tok + kTileT - 1) / kTileT);
   int i = 0;
   while (i < n_layers) {
-    // one launch per run of layers with the same kernel mode, at most kMaxLayersPerLaunch
+    // one launch per run of layers with the same kernel mode, at most per_launch of them
     LayerBatch batch{};
     const int mode = layer_mode(ctx, ctx->layers[layer_begin + i]);
     int n = 0;
-    while (i + n < n_layers && n < kMaxLayersPerLaunch &&
+    while (i + n < n_layers && n < per_launch &&
            layer_mode(ctx, ctx->layers[layer_begin + i + n]) == mode) {
       const hc_layer_state& L = ctx->layers[layer_begin + i + n];
       batch.e[n] = LayerEntry{static_cast<const uint16_t*>(d_hidden[i + n]), L.wpack, L.affine, L.pool,

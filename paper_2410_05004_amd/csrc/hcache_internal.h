@@ -37,6 +37,7 @@ __host__ __device__ inline int swz_w(int row) { return (row >> 1) & 3; }
 __host__ __device__ inline int swz_x(int row) { return (row >> 1) & 7; }
 
 inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+constexpr int kChipCUs = 256;     // one workgroup of the restoration kernel per CU at a time
 
 // Tile scheduling.  Workgroup ids are handed to the 8 XCDs round-robin and every XCD has
 // its own L2, so the tiles one XCD works on at the same time should share weight rows
@@ -111,7 +112,6 @@ inline int choose_tile_grid(int nf, int nt, TileGrid& g) {
 // unsplit round.
 // n is the cheapest of 2 .. min(256 / t, nm / 8, 16) (one round of split workgroups, shares of
 // at least 512 channels); the plan is used when it is cheaper than the round, or on request.
-constexpr int kChipCUs = 256;
 constexpr int kSplitSlotFloats = kTileF * kTileT + 512;   // accumulators, 256 sums of squares, 256 plain sums
 constexpr int kSplitMaxSlots = 256;                       // slots of the workspace (one round of workgroups)
 constexpr int kSplitMinSuper = 8;                         // least share of the loop: 8 x 64 channels
@@ -196,10 +196,17 @@ struct LayerEntry {
   uint16_t* pool;
   int64_t num_pages;
 };
-// 8 layers per launch: enough rounds of workgroups to hide the gaps between kernels, few
-// enough that the CUs of an XCD stay close together and keep sharing weights in its L2
-// (measured: 16 and 32 layers per launch fetch 4 % and 37 % more, and are no faster)
-constexpr int kMaxLayersPerLaunch = 8;
+// Layers per launch.  8 when a layer fills a good part of the chip: enough rounds of
+// workgroups to hide the gaps between kernels, few enough that the CUs of an XCD stay close
+// together and keep sharing weights in its L2 (measured at 256 tiles per layer: 16 and 32
+// layers per launch fetch 4 % and 37 % more, and are no faster).  When a layer has fewer than
+// 32 tiles (a short context), as many layers as fill one round of 256 workgroups, up to 32:
+// a launch takes a round's time however few of the CUs it uses.
+constexpr int kMaxLayersPerLaunch = 32;
+inline int layers_per_launch(int nf, int nt) {
+  const int by_round = kChipCUs / (nf * nt);
+  return by_round < 8 ? 8 : by_round > kMaxLayersPerLaunch ? kMaxLayersPerLaunch : by_round;
+}
 struct LayerBatch {
   LayerEntry e[kMaxLayersPerLaunch];
   int32_t slots_per_layer;     // workgroups per layer (a multiple of 8); set by launch_restore

@@ -309,6 +309,79 @@ def test_streamed_workloads_full_depth(hc, index, layers, sampled_layers):
     store.destroy()
 
 
+@pytest.mark.parametrize("index,n_layers,sampled", [(2, 10, (0, 3, 7, 9)), (5, 8, (0,))],
+                         ids=["llama3-8b-gqa-T8192-10-layers", "opt30b-T2048-8-layers"])
+def test_layers_per_launch_full_size(hc, index, n_layers, sampled):
+    """hc_restore_kv_layers at full size, the launch configuration bench.py times: hidden states
+    of all layers resident in HBM, eight layers per launch (workload 2: 10 layers = a launch
+    of eight and one of two; 256 tiles per layer, the XCD a super tile goes to rotating with
+    the layer; workload 5: 448 tiles per layer, LayerNorm + biases, no rotation).  A different
+    seeded input per layer; every layer equals bit for bit what one hc_restore_kv launch for
+    that layer writes, and passes the exact written-set check and the random projection over
+    all tokens; the sampled ones are also compared element by element (workload 2: ~1100 rows;
+    workload 5: the rows of test_gpu_variants.py::test_opt30b_shape -- the tolerance sits at the
+    edge of bf16 output rounding, and 16 M outputs of this LayerNorm shape reach 2.2e-2)."""
+    import torch
+    w = syn.WORKLOADS[index]
+    T, B = w.tokens, w.block_size
+    layer_norm = w.norm == "layer"
+    desc = gh.make_desc(hc, n_layers=n_layers, d_model=w.d_model, n_q_heads=w.n_q_heads,
+                        n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, block_size=B,
+                        max_position=w.pos_offset + T, rope_theta=w.rope_theta, rms_eps=w.rms_eps,
+                        rope_style=w.rope_style, norm_kind=1 if layer_norm else 0)
+    ctx = hc.Context(desc)
+    s = gh.stream_handle()
+    bt, num_pages = syn.block_table(w, w.pos_offset + T)
+    d_bt = gh.to_dev_i32(bt)
+    pos = (w.pos_offset + np.arange(T)).astype(np.int32)
+    d_pos = gh.to_dev_i32(pos)
+    data, hidden_dev, pools = [], [], []
+    for l in range(n_layers):
+        wkv, gamma = syn.layer_weights(w, l)
+        x = syn.layer_hidden(w, l)
+        beta = bias = None
+        if layer_norm:
+            beta, bias = syn.layer_affine(w, l)
+            ctx.set_layer_weights_affine(l, gh.to_dev_bf16(wkv), gh.to_dev_bf16(gamma), gh.to_dev_bf16(beta),
+                                         gh.to_dev_bf16(bias), s)
+        else:
+            ctx.set_layer_weights(l, gh.to_dev_bf16(wkv), gh.to_dev_bf16(gamma), s)
+        torch.cuda.synchronize()
+        data.append((wkv, gamma, x, beta, bias))
+        hidden_dev.append(gh.to_dev_bf16(x))
+        pools.append(gh.new_pool(num_pages, B, w.n_kv_heads, w.head_dim))
+        ctx.set_kv_pool(l, pools[l], num_pages)
+    print(f"{w.name}: {n_layers} layers resident", flush=True)
+    ctx.timing_begin()
+    ctx.restore_kv_layers(0, hidden_dev, d_pos, T, d_bt, len(bt), s)
+    _, launches = ctx.timing_end(s)
+    assert launches == -(-n_layers // 8)
+    assert ctx.poll_device_error(s) == 0
+    torch.cuda.synchronize()
+    if layer_norm:
+        rng = np.random.default_rng(55)
+        rows = sample_rows(rng, T, [256 * i for i in range(1, T // 256)], range(B), range(T - B, T), 256)
+    else:
+        rng = np.random.default_rng([98, index])
+        rows = sample_rows(rng, T, range(256, T, 256), range(0, B - w.pos_offset % B), range(T - 16, T))
+    ctx.set_split(0)
+    for l in range(n_layers):
+        wkv, gamma, x, beta, bias = data[l]
+        alone = gh.new_pool(num_pages, B, w.n_kv_heads, w.head_dim)
+        ctx.set_kv_pool(l, alone, num_pages)
+        ctx.restore_kv(l, hidden_dev[l], d_pos, T, d_bt, len(bt), s)
+        assert ctx.poll_device_error(s) == 0
+        assert torch.equal(alone.view(torch.int16), pools[l].view(torch.int16)), \
+            f"layer {l}: the launch over several layers differs from the single-layer launch"
+        del alone
+        res = check_layer(w, desc, gh.pool_bits(pools[l]), x, wkv, gamma, pos, np.zeros(T, dtype=np.int64),
+                          bt[None, :], rows if l in sampled else None, rng, beta_bits=beta, bias_bits=bias)
+        print(f"{w.name} layer {l}: sampled worst {res[0]:.3e} x RMS_head; projection check "
+              f"K {res[1]:.3f} V {res[2]:.3f} of limit", flush=True)
+        pools[l] = None
+    ctx.destroy()
+
+
 def test_ragged_workload(hc):
     """Workload 3: 16 contexts of 512..4096 tokens in one ragged launch per layer."""
     import torch

@@ -182,10 +182,11 @@ def test_layers_in_one_launch(hc, norm_kind):
     ctx.restore_kv_layers(0, hidden, d_pos, T, d_bt, n_blocks, s)
     _, launches = ctx.timing_end(s)
     assert ctx.poll_device_error(s) == 0
+    # two tiles per layer: up to 32 layers go into one launch (short contexts fill the chip with layers)
     if norm_kind == 1:
-        assert launches == 5                              # one mode: 8 + 8 + 8 + 8 + 3 layers
+        assert launches == 2                              # one mode: 32 + 3 layers
     else:
-        assert launches > 5                               # the mode changes with the bias
+        assert launches > 2                               # the mode changes with the bias
     for l in (0, 1, 2, 3, 17, 31, 32, 34):
         a, b = gh.pool_bits(pools_a[l]), gh.pool_bits(pools_b[l])
         assert np.array_equal(a, b), f"layer {l}: fused launch differs from the single-layer launch"
