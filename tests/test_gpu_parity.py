@@ -315,14 +315,18 @@ def test_host_side_errors(hc, torch):
     ctx.destroy()
 
 
-@pytest.mark.parametrize("pinned,loader", [(True, 0), (True, 1), (False, 0)],
-                         ids=["copy-engines", "gather-kernel", "pageable-store"])
-def test_restore_context_from_store(hc, torch, pinned, loader):
+@pytest.mark.parametrize("pinned,loader,d_model", [(True, 0, 512), (True, 1, 512), (False, 0, 512), (True, 0, 2048)],
+                         ids=["copy-engines", "gather-kernel", "pageable-store", "split-launches"])
+def test_restore_context_from_store(hc, torch, pinned, loader, d_model):
     """Whole-context pipelined restore from the chunk store: all layers, a token range that
     starts and ends inside chunks, positions offset so the first page is part filled; with
-    the gather-kernel loader, the hipMemcpyAsync loader, and a store in pageable memory."""
+    the gather-kernel loader, the hipMemcpyAsync loader, and a store in pageable memory.  At
+    d_model 2048 every layer's launch is a split launch (six tiles, four shares each, then the
+    finishing launch), so the loader's events interleave with two kernels per layer that
+    share the context's workspace."""
     rng = np.random.default_rng(31)
-    L, d_model, n_kv, hd, B, CT = 5, 512, 2, 128, 16, 64
+    L, n_kv, hd, B, CT = 5, 2, 128, 16, 64
+    assert hc.diag_split_plan(d_model, n_kv * hd, 650)["n_split"] == (4 if d_model == 2048 else 1)
     T_stored, tok_begin, n_tok, pos_offset = 700, 30, 650, 1000
     desc = gh.make_desc(hc, n_layers=L, d_model=d_model, n_q_heads=n_kv, n_kv_heads=n_kv,
                         head_dim=hd, block_size=B, max_position=pos_offset + T_stored)

@@ -103,3 +103,13 @@ def test_inputs_of_the_split_launch_tests_are_feasible():
         r = feasible(case.x[rows], case.gamma, case.wkv, pos[rows], c["n_kv"], c["hd"], theta=500000.0)
         print(f"whole + split tiles {name}, {len(rows)} rows checked element by element: model error {r:.4f} x RMS_head")
         assert r <= MARGIN * TOL
+
+
+def test_inputs_of_the_store_restore_test_at_the_split_width_are_feasible():
+    import test_gpu_parity  # noqa: F401  (the test draws LayerCase([31, layer]) at d_model 2048, tokens 30..679)
+    pos = 1000 + 30 + np.arange(650)
+    for l in range(5):
+        c = gh.LayerCase(np.random.default_rng([31, l]), 2048, 2, 128, 700)
+        r = feasible(c.x[30:680], c.gamma, c.wkv, pos, 2, 128)
+        print(f"store restore at d_model 2048, layer {l}: model error {r:.4f} x RMS_head")
+        assert r <= MARGIN * TOL
