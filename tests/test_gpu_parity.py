@@ -158,6 +158,51 @@ def test_split_launch_against_oracle(hc, torch, d_model, n_kv, hd, n_tok, style,
         print(f"split={split}: worst err = {worst * gh.TOL:.3e} x RMS_head", flush=True)
 
 
+def test_split_and_unsplit_launches_agree_on_random_shapes(hc, torch):
+    """Twenty seeded shapes (odd numbers of feature tiles, padded K/V parts, ragged token tiles,
+    one to twelve tiles split two to sixteen ways, all three RoPE styles): the split launch
+    writes exactly the cache elements the unsplit launch writes, and every value within one
+    bf16 step of it, or, for values that are small because their terms cancel, within 2^-9 of
+    the RMS of all values (the two differ only in the order of fp32 additions).  The unsplit
+    kernel is the one the other tests hold against the oracle at many shapes."""
+    rng = np.random.default_rng(2024)
+    done = 0
+    while done < 20:
+        d_model = int(rng.choice([1024, 2048, 4096, 8192]))
+        hd = int(rng.choice([64, 128]))
+        n_kv = int(rng.integers(1, 7))
+        n_tok = int(rng.integers(1, 900))
+        style = int(rng.integers(0, 3))
+        plan = hc.diag_split_plan(d_model, n_kv * hd, n_tok, 2)
+        if not plan["split"]:
+            continue
+        done += 1
+        case = gh.LayerCase(rng, d_model, n_kv, hd, n_tok)
+        B = 16
+        offset = int(rng.integers(0, 64))
+        n_blocks = (offset + n_tok + B - 1) // B
+        num_pages = n_blocks + 3
+        bt = rng.permutation(num_pages)[:n_blocks].astype(np.int32)
+        pos = (offset + rng.permutation(n_tok)).astype(np.int32)
+        desc = gh.make_desc(hc, n_layers=1, d_model=d_model, n_q_heads=n_kv, n_kv_heads=n_kv, head_dim=hd,
+                            block_size=B, max_position=offset + n_tok, rope_style=style)
+        got = []
+        for split in (2, 0):
+            bits, flags = run_single(hc, torch, case, desc, pos, bt, num_pages, split=split)
+            assert flags == 0
+            got.append(bits)
+        a, b = got
+        assert np.array_equal(a != gh.SENTINEL, b != gh.SENTINEL), (d_model, n_kv, hd, n_tok, style)
+        m = a != gh.SENTINEL
+        assert m.sum() == 2 * n_tok * n_kv * hd
+        fa, fb = syn.bf16_bits_to_f64(a[m]), syn.bf16_bits_to_f64(b[m])
+        step = np.maximum(np.abs(fa), np.abs(fb)) * 2.0 ** -7          # one bf16 step at the larger magnitude
+        bad = np.abs(fa - fb) > np.maximum(step, np.sqrt(np.mean(fb * fb)) * 2.0 ** -9)
+        assert not bad.any(), (d_model, n_kv, hd, n_tok, style, int(bad.sum()))
+        print(f"d_model {d_model} heads {n_kv} x {hd} tokens {n_tok} style {style}: {plan['n_tail']} tiles x "
+              f"{plan['n_split']}; {np.mean(a[m] == b[m]):.4f} of the values bit-identical", flush=True)
+
+
 def test_block_sizes(hc, torch):
     for B in (8, 32):
         rng = np.random.default_rng([5, B])
