@@ -108,6 +108,9 @@ def main():
     ap.add_argument("--d-model", type=int, default=None,
                     help="diagnostic: override the workload's d_model (a multiple of 64) to separate the cost "
                          "per channel from the fixed cost per tile; implies a different synthetic shape")
+    ap.add_argument("--split", type=int, default=1,
+                    help="hc_set_split mode for single-layer launches: 0 never split the d_model loop, "
+                         "1 (default) when the library's cost model says it pays, 2 whenever possible")
     ap.add_argument("--tokens", type=int, default=None,
                     help="diagnostic: override the workload's token count (single-context workloads): short "
                          "contexts, where a layer fills only part of the chip")
@@ -181,6 +184,7 @@ def main():
                         w.rope_theta, w.rms_eps,
                         hc.HC_NORM_LAYER if w.norm == "layer" else hc.HC_NORM_RMS)
     ctx = hc.Context(desc)
+    ctx.set_split(args.split)
     stream = torch.cuda.current_stream().cuda_stream
 
     def dev_bf16(bits):

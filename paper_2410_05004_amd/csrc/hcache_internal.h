@@ -412,12 +412,13 @@ inline bool for_each_run(const hc_store* st, const std::vector<int64_t>& chunks,
   return true;
 }
 
+// Every run goes out in the two-dimensional form, a single piece as one row: measured here, a
+// plain hipMemcpyAsync of a few MiB from the pinned arena is served several times slower than
+// the same bytes as a 2D copy while the restoration kernel occupies the CUs (256 tokens of the
+// Llama-3-8B shape, one 2 MiB chunk per layer: 8.6 ms per restore against 1.8 ms).
 inline hc_status enqueue_run(const CopyRun& r, hipStream_t xs) {
-  if (r.rows == 1 || r.pitch == r.row_bytes)
-    HC_HIP(hipMemcpyAsync(r.dst, r.src, r.row_bytes * r.rows, hipMemcpyHostToDevice, xs));
-  else
-    HC_HIP(hipMemcpy2DAsync(r.dst, r.row_bytes, r.src, r.pitch, r.row_bytes, r.rows,
-                            hipMemcpyHostToDevice, xs));
+  const size_t pitch = r.rows == 1 ? r.row_bytes : r.pitch;
+  HC_HIP(hipMemcpy2DAsync(r.dst, r.row_bytes, r.src, pitch, r.row_bytes, r.rows, hipMemcpyHostToDevice, xs));
   return HC_OK;
 }
 

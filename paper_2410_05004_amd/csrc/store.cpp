@@ -362,7 +362,7 @@ static hc_status restore_context_impl(hc_ctx* ctx, const hc_store* hs, const hc_
   };
 
   // The gather kernel needs device-readable arenas and reads its segment table from pinned
-  // host memory; a pageable arena goes through hipMemcpyAsync.
+  // host memory; a pageable arena goes through the copy calls.
   const bool use_gather = ctx->loader_mode == 1 && (l_h == 0 || hs->pinned) && (l_h == L || ks->pinned);
   CopySegment* tab = nullptr;
   size_t tab_used = 0;
