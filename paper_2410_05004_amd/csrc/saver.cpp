@@ -313,7 +313,8 @@ static hc_status save_layer_impl(hc_saver* sv, int32_t layer, const void* d_hidd
         e = hipMemcpy2DAsync(pc[i].dst, pitch, src + pc[i].src_off, pc[i].bytes, pc[i].bytes, j - i,
                              hipMemcpyDeviceToHost, ds);
       } else {
-        e = hipMemcpyAsync(pc[i].dst, src + pc[i].src_off, pc[i].bytes, hipMemcpyDeviceToHost, ds);
+        e = hipMemcpy2DAsync(pc[i].dst, pc[i].bytes, src + pc[i].src_off, pc[i].bytes, pc[i].bytes, 1,
+                             hipMemcpyDeviceToHost, ds);
       }
       i = j;
     }
@@ -323,8 +324,8 @@ static hc_status save_layer_impl(hc_saver* sv, int32_t layer, const void* d_hidd
   if (e == hipSuccess && !small.empty()) {
     // snapshot the sub-range of the batch that holds the remaining rows (pieces are in batch order)
     const size_t lo = small.front().src_off, hi = small.back().src_off + small.back().bytes;
-    e = hipMemcpyAsync(sv->slot_buf[slot], static_cast<const unsigned char*>(d_hidden) + lo, hi - lo,
-                       hipMemcpyDeviceToHost, ds);
+    e = hipMemcpy2DAsync(sv->slot_buf[slot], hi - lo, static_cast<const unsigned char*>(d_hidden) + lo, hi - lo,
+                         hi - lo, 1, hipMemcpyDeviceToHost, ds);
     for (StorePiece& q : small) q.src_off -= lo;
   }
   job->pieces.swap(small);
