@@ -210,13 +210,16 @@ hc_status hc_store_drop(hc_store* store, int64_t seq_id);
 /* Restore ALL layers of tokens [tok_begin, tok_begin + n_tok) of one stored context,
  * token i sitting at absolute position pos_offset + i (Section 3.1 pipeline; Section 5
  * "Pipelined state transmission").  Per layer the chunks are copied to one of two HBM
- * staging buffers on `copy_stream` -- by the copy engines, one (strided) hipMemcpy2DAsync /
- * hipMemcpyAsync per run of equally spaced chunks, or by a gather kernel that reads the
- * pinned arena over the host link (hc_set_loader) -- and the restoration kernel runs on
- * `compute_stream`; events order the two so that the transfer of layer L+1 overlaps the
- * kernel of layer L.  Staging buffers are allocated inside the call when the context has
- * none large enough.  Returns after everything is enqueued; the caller synchronises
- * `compute_stream`.  The two streams must differ. */
+ * staging buffers -- by the copy engines, one (strided) hipMemcpy2DAsync per run of equally
+ * spaced chunks, even layers on `copy_stream` and odd layers on a second copy stream the
+ * context owns (so that the fixed cost of one transfer overlaps the bytes of the other), or by
+ * a gather kernel on `copy_stream` that reads the pinned arena over the host link
+ * (hc_set_loader) -- and the restoration kernel runs on `compute_stream`; events order them so
+ * that the transfer of layer L+1 overlaps the kernel of layer L.  Staging buffers (and the
+ * second stream) are created inside the call when the context has none.  Returns after
+ * everything is enqueued; every copy is complete once `compute_stream` has run dry, which is
+ * what the caller synchronises (not `copy_stream` alone) before it changes the store.  The two
+ * streams must differ. */
 hc_status hc_restore_context(hc_ctx* ctx, const hc_store* store, int64_t seq_id,
                              int32_t tok_begin, int32_t n_tok, int32_t pos_offset,
                              const int32_t* d_block_table, int32_t n_blocks,

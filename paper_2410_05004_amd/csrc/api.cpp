@@ -260,6 +260,7 @@ hc_status hc_destroy(hc_ctx* ctx) {
   if (ctx->err_dev) (void)hipFree(ctx->err_dev);
   if (ctx->split_ws) (void)hipFree(ctx->split_ws);
   if (ctx->split_done) (void)hipEventDestroy(ctx->split_done);
+  if (ctx->copy2) (void)hipStreamDestroy(ctx->copy2);
   for (int i = 0; i < 2; ++i) {
     if (ctx->stage[i]) (void)hipFree(ctx->stage[i]);
     if (ctx->h2d_done[i]) (void)hipEventDestroy(ctx->h2d_done[i]);

